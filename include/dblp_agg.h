@@ -1,0 +1,184 @@
+/*
+ * dblp_agg -- receiver-side bounded-loss gradient aggregation of DBLP
+ * (Dynamic Bounded-Loss Protocol) on one AMD MI355X (gfx950).
+ *
+ * One context models the parameter server of the paper's centralized
+ * all-reduce for one communication round at a time: packets from W workers
+ * arrive in any order over a lossy channel, are validated and scattered into
+ * an accumulator (Alg. "DBLP_RECV"), loss is counted against the current
+ * tolerance to decide what must be retransmitted (Sec. "Dynamically Changing
+ * Loss Tolerance"), unreceived chunks stay zero and the mean over all workers
+ * is formed (Alg. "DBLP_RECV" last statements, Alg. "Server"), and the L2 norm
+ * of that mean drives critical-regime detection (Eq. 1).
+ *
+ * Conventions
+ *   - Every call returns DBLP_OK (0) or a negative DBLP_E* code; nothing
+ *     throws, aborts or prints.  dblp_last_error() gives a short text.
+ *   - d_* arguments are DEVICE pointers owned by the caller; the library never
+ *     frees them and does not keep them after the call returns (the kernels
+ *     that read them are ordered on the context's stream).  h_* arguments are
+ *     HOST pointers.  Anything else is passed by value.
+ *   - All work is enqueued on the hipStream_t given at creation (passed as
+ *     void*).  Calls are asynchronous except those that return host scalars
+ *     (dblp_loss_account, dblp_phase_signal, dblp_get_counters,
+ *     dblp_packetize), which synchronise that stream.
+ *   - A context is not thread-safe; use one per host thread.
+ *
+ * Geometry.  The gradient has N fp32 elements, tiled in order by B buckets
+ * (e.g. one per tensor, Sec. "Metadata": layer names and chunk counts are
+ * exchanged once before training; here they arrive as the bucket table).  A
+ * bucket of c elements is cut into ceil(c / P) packets of P floats, the last
+ * one short; packets never straddle buckets.  Sequence numbers run bucket-major
+ * from 0 to n_pkts - 1 for every worker.
+ *
+ * Wire packet (Sec. "Metadata": sequence number, round counter, data length;
+ * field widths are this library's choice), little-endian, `stride` bytes apart
+ * with stride = 8 + 4P rounded up to 16:
+ *     uint32 seq; uint16 round; uint16 len_floats; float payload[len_floats]; zero padding
+ * With P = 366 the stride is 1472 bytes, the UDP payload of a 1500-byte MTU.
+ * The worker a packet came from is not in the header (the paper identifies it
+ * by the UDP port): it is given per slot in d_src_worker.
+ */
+#ifndef DBLP_AGG_H
+#define DBLP_AGG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DBLP_OK 0
+#define DBLP_EINVAL (-1)    /* bad argument (null, out of range, misaligned) */
+#define DBLP_ENOMEM (-2)    /* host or device allocation failed */
+#define DBLP_ECAPACITY (-3) /* retransmit list longer than the caller's buffer (count still valid) */
+#define DBLP_ESTATE (-4)    /* call out of order (e.g. apply before begin_round) */
+#define DBLP_EHIP (-5)      /* a HIP call failed; see dblp_last_error() */
+
+#define DBLP_COMP_ZEROFILL_MEAN 0 /* the paper's compensation: missing = 0, divide by all W */
+
+#define DBLP_MAX_WORKERS 64
+
+typedef struct dblp_ctx dblp_ctx;
+
+typedef struct {
+    uint64_t elem_offset; /* first element; buckets must tile [0, n_elems) in order */
+    uint64_t elem_count;  /* > 0, < 2^32 */
+} dblp_bucket;
+
+typedef struct {
+    uint32_t n_workers;      /* W, 1..DBLP_MAX_WORKERS */
+    uint32_t payload_floats; /* P, 1..65535 */
+    uint64_t n_elems;        /* N */
+    uint32_t n_buckets;      /* B */
+    const dblp_bucket* buckets; /* HOST array of B entries, copied */
+    double eta;              /* Eq. 1 threshold; the paper uses 0.5 */
+    int device;              /* HIP device ordinal */
+    void* stream;            /* hipStream_t; NULL = the null stream */
+} dblp_config;
+
+/* Allocates the context and its device state (bitmap W x ceil(n_pkts/64) words, arrival
+ * index W x n_pkts x 8 bytes, accumulator N floats, per-bucket counters).  *out is set only
+ * on success.  Errors: EINVAL (bad table, W too large, n_pkts >= 2^32), ENOMEM, EHIP. */
+int dblp_create(dblp_ctx** out, const dblp_config* cfg);
+
+/* Frees everything the context owns.  NULL is accepted. */
+int dblp_destroy(dblp_ctx* ctx);
+
+/* Sizes a caller needs to allocate buffers: packets per worker per round, wire stride in
+ * bytes, bitmap words per worker.  Any output pointer may be NULL. */
+int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* packet_stride_bytes,
+                uint64_t* bitmap_words_per_worker);
+
+/* Alg. "DBLP_RECV", initialisation: empty bitmap, nothing received, counters zero; `round`
+ * is the round counter that arriving packets must carry.  The accumulator is not cleared:
+ * a packet's first arrival overwrites its span and dblp_finalize writes zeros for spans
+ * that never arrived, which gives the same result as a zero-initialised buffer. */
+int dblp_begin_round(dblp_ctx* ctx, uint16_t round);
+
+/* Sender side (Alg. "DBLP Send": split data into chunks).  Not part of the timed receiver
+ * path.  d_grad holds elements [elem_base, elem_base + n_grad_elems) of worker w's gradient.
+ * Packets first_seq .. first_seq + n_pkts - 1 are written; packet i goes to slot
+ * d_slot_map[i] (device array, may be NULL: slot_base + i).  Slots must be < n_slots
+ * (the capacity of d_packets in packets and of d_src_worker in entries); a slot outside is
+ * skipped and the call returns EINVAL.  `round` is written into the headers.
+ * Errors: EINVAL if the packets' elements are not inside the gradient window. */
+int dblp_packetize(dblp_ctx* ctx, uint32_t w, uint16_t round, const float* d_grad,
+                   uint64_t elem_base, uint64_t n_grad_elems, uint64_t first_seq, uint64_t n_pkts,
+                   const uint32_t* d_slot_map, uint64_t slot_base, uint64_t n_slots,
+                   void* d_packets, uint16_t* d_src_worker);
+
+/* Alg. "DBLP_RECV", chunk-arrival branch, for one batch of arrivals (property 1 of the
+ * paper: packets are applied as they arrive, in any order).
+ *   d_packets     n_slots wire packets, 16-byte aligned, `stride` bytes apart
+ *   d_src_worker  n_slots entries: worker each slot's packet arrived from
+ *   d_mask_words  ceil(n_slots/64) words, bit s%64 of word s/64 = slot s survived the
+ *                 network; a lost slot is never read.  NULL = all survived.
+ *   d_order       n_arrivals entries, d_order[k] = slot of the k-th arrival; a slot may
+ *                 appear any number of times.  NULL = identity (then n_arrivals <= n_slots).
+ * Per arrival: round != current -> stale (Sec. "Bounded-Loss-Tolerant Transmission");
+ * worker, seq or length inconsistent with the geometry, or slot >= n_slots -> invalid;
+ * already in the bitmap -> duplicate; otherwise accepted: bitmap bit set and payload added
+ * to the accumulator.  If two copies of one packet arrive in the same batch the earlier
+ * arrival is used.  The sum over workers of one packet is formed in worker order, so the
+ * result does not depend on the arrival permutation.  Requires begin_round. */
+int dblp_apply_arrivals(dblp_ctx* ctx, const void* d_packets, const uint16_t* d_src_worker,
+                        uint64_t n_slots, const uint64_t* d_mask_words, const uint32_t* d_order,
+                        uint64_t n_arrivals);
+
+/* One probe (Alg. "DBLP_RECV" probe branch; Sec. "Dynamically Changing Loss Tolerance":
+ * retransmission stops once missing/total <= p, and only lost packets are resent).
+ * For every (worker w, bucket b): missing = packets of b not in w's bitmap; the pair meets
+ * the tolerance iff missing <= floor(bound_ppm * n_b / 10^6).  The retransmit list is every
+ * missing (w, seq) of every pair that does not meet it, encoded (w << 32) | seq, ascending.
+ *   d_missing      [W*B] counts, index w*B + b; may be NULL
+ *   d_retx_list    retx_capacity entries; may be NULL iff retx_capacity == 0
+ *   h_retx_count   full list length (even when it exceeds the capacity)
+ *   h_all_met      1 iff the list is empty
+ * Returns ECAPACITY if the list was truncated to retx_capacity entries. */
+int dblp_loss_account(dblp_ctx* ctx, uint32_t bound_ppm, uint32_t* d_missing, uint64_t* d_retx_list,
+                      uint64_t retx_capacity, uint64_t* h_retx_count, int* h_all_met);
+
+/* Alg. "DBLP_RECV" last statements + Alg. "Server" mean: d_out[e] = acc[e] / W where
+ * unreceived chunks count as zero (a span no worker delivered is exactly 0).  d_out: N
+ * floats.  Also accumulates sum(d_out^2) for dblp_phase_signal.  Only
+ * DBLP_COMP_ZEROFILL_MEAN is defined by the paper; other values give EINVAL. */
+int dblp_finalize(dblp_ctx* ctx, int compensation, float* d_out);
+
+/* Eq. 1: norm = ||G_curr||_2 of the aggregated gradient; rel_delta = | ||G_prev|| - norm | /
+ * ||G_prev||; critical = rel_delta >= eta.  With no previous norm (or a zero one) rel_delta
+ * is +inf and critical is 1 (training starts in the critical regime).  The stored previous
+ * norm is replaced by `norm`.  d_vec == NULL uses the sum of squares produced by the last
+ * dblp_finalize of this round (ESTATE if there was none); otherwise d_vec is N floats,
+ * 16-byte aligned, and is reduced here. */
+int dblp_phase_signal(dblp_ctx* ctx, const float* d_vec, double* h_norm, double* h_rel_delta,
+                      int* h_critical);
+
+/* Copies the bitmap, W x bitmap_words_per_worker words, bit seq%64 of word seq/64. */
+int dblp_get_bitmap(dblp_ctx* ctx, uint64_t* d_bitmap_out);
+
+/* h_counters = {accepted, duplicate, stale, invalid} since begin_round. */
+int dblp_get_counters(dblp_ctx* ctx, uint64_t h_counters[4]);
+
+/* The only state that survives a round: ||G_prev||.  have = 0 means "none yet". */
+int dblp_set_prev_norm(dblp_ctx* ctx, double norm, int have);
+int dblp_get_prev_norm(const dblp_ctx* ctx, double* h_norm, int* h_have);
+
+/* Text of the last error on this context (valid until the next call on it). */
+const char* dblp_last_error(const dblp_ctx* ctx);
+
+/* Tolerance policies: host scalars that turn the phase signal into the next bound (ppm).
+ * two_level is the paper's rule (Sec. "Centralized All-Reduce Architecture", Table 1):
+ * critical -> P_low, otherwise P_high = P_low + k; the first iteration is critical.
+ * three_level and linear are extensions for workloads that step through more levels:
+ *   three_level: delta >= eta -> tight; eta/2 <= delta < eta -> mid; else loose
+ *   linear:      hi - (hi - lo) * min(delta/eta, 1), rounded to a multiple of 1000 ppm */
+uint32_t dblp_policy_two_level(int critical, uint32_t p_low_ppm, uint32_t p_high_ppm);
+uint32_t dblp_policy_three_level(double rel_delta, double eta, uint32_t tight_ppm, uint32_t mid_ppm,
+                                 uint32_t loose_ppm);
+uint32_t dblp_policy_linear(double rel_delta, double eta, uint32_t lo_ppm, uint32_t hi_ppm);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DBLP_AGG_H */

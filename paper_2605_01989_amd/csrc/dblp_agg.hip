@@ -1,0 +1,871 @@
+// Receiver-side bounded-loss gradient aggregation of DBLP on gfx950 (MI355X).
+// Kernels and the C-ABI declared in include/dblp_agg.h.
+//
+// Data flow of one arrival batch (Alg. "DBLP_RECV", chunk-arrival branch):
+//   index_arrivals  one thread per arrival: header parse, validation, and an
+//                   atomicMin of (arrival rank << 32 | slot) into the arrival
+//                   index `pending[w][seq]`  (integer work, a few bytes per packet)
+//   gather_accumulate  one wave per run of consecutive sequence numbers: reads
+//                   the index, sets bitmap bits, then streams the payloads of
+//                   that packet from all workers (16-byte loads, worker order)
+//                   into registers and writes the accumulator span once.
+// Every payload byte is read exactly once and the accumulator is written once
+// per batch that touches it; there are no floating-point atomics, so the sum
+// is independent of the arrival permutation.
+//
+// The probe (Sec. "Dynamically Changing Loss Tolerance"): loss_count (ballot-free
+// popcount of bitmap words + DPP wave reduction), scan_need (exclusive prefix of
+// the per-(worker,bucket) list lengths) and emit_retx (ordered compaction).
+// finalize_mean applies the zero-fill/mean of Alg. "Server" and produces the
+// partial sums of squares that Eq. 1 needs; reduce_partials finishes the norm.
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/dblp_agg.h"
+
+typedef unsigned long long u64;
+typedef uint32_t u32;
+
+#define NONE64 0xFFFFFFFFFFFFFFFFull
+#define WAVE 64
+
+// device counters (u64 each)
+enum { C_ACCEPTED = 0, C_DUP_PREV, C_STALE, C_INVALID, C_CANDIDATES, C_LO, C_HI, C_PKT_BAD, C_COUNT };
+
+struct Geo {
+    const u32* first_seq;   // [B+1]
+    const u64* b_off;       // [B]
+    const u64* b_cnt;       // [B]
+    u32 B, P, W;
+    u32 n_pkts;
+    u32 stride;             // bytes
+    u32 units;              // stride / 16
+    u32 run;                // consecutive seqs handled together by one wave: max(1, 64 / W)
+    u64 words_pw;           // bitmap words per worker
+};
+
+// ------------------------------------------------------------------------------------------
+// wave-level primitives (64 lanes): DPP moves, reductions and scans
+// ------------------------------------------------------------------------------------------
+#define DPP_ROW_SHR(n) (0x110 + (n))
+#define DPP_ROW_BCAST15 0x142
+#define DPP_ROW_BCAST31 0x143
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ u32 dpp_u32(u32 identity, u32 v) {
+    return (u32)__builtin_amdgcn_update_dpp((int)identity, (int)v, CTRL, ROW_MASK, 0xF, false);
+}
+
+struct OpAdd { static __device__ __forceinline__ u32 id() { return 0u; } static __device__ __forceinline__ u32 f(u32 a, u32 b) { return a + b; } };
+struct OpMin { static __device__ __forceinline__ u32 id() { return 0xFFFFFFFFu; } static __device__ __forceinline__ u32 f(u32 a, u32 b) { return a < b ? a : b; } };
+struct OpMax { static __device__ __forceinline__ u32 id() { return 0u; } static __device__ __forceinline__ u32 f(u32 a, u32 b) { return a > b ? a : b; } };
+
+// Inclusive scan over the 64 lanes; all lanes must be active.  Lane 63 ends with the total.
+template <class Op>
+__device__ __forceinline__ u32 wave_scan_incl(u32 v) {
+    v = Op::f(v, dpp_u32<DPP_ROW_SHR(1), 0xF>(Op::id(), v));
+    v = Op::f(v, dpp_u32<DPP_ROW_SHR(2), 0xF>(Op::id(), v));
+    v = Op::f(v, dpp_u32<DPP_ROW_SHR(4), 0xF>(Op::id(), v));
+    v = Op::f(v, dpp_u32<DPP_ROW_SHR(8), 0xF>(Op::id(), v));
+    v = Op::f(v, dpp_u32<DPP_ROW_BCAST15, 0xA>(Op::id(), v));
+    v = Op::f(v, dpp_u32<DPP_ROW_BCAST31, 0xC>(Op::id(), v));
+    return v;
+}
+
+template <class Op>
+__device__ __forceinline__ u32 wave_reduce(u32 v) {
+    return (u32)__builtin_amdgcn_readlane((int)wave_scan_incl<Op>(v), 63);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double v) {
+    u64 bits = (u64)__double_as_longlong(v);
+    u32 lo = dpp_u32<CTRL, ROW_MASK>(0u, (u32)bits);
+    u32 hi = dpp_u32<CTRL, ROW_MASK>(0u, (u32)(bits >> 32));
+    return __longlong_as_double((long long)(((u64)hi << 32) | lo));   // identity 0.0 = all-zero bits
+}
+
+// Sum of a double over the 64 lanes (all active); every lane gets the total.
+__device__ __forceinline__ double wave_sum_f64(double v) {
+    v += dpp_f64<DPP_ROW_SHR(1), 0xF>(v);
+    v += dpp_f64<DPP_ROW_SHR(2), 0xF>(v);
+    v += dpp_f64<DPP_ROW_SHR(4), 0xF>(v);
+    v += dpp_f64<DPP_ROW_SHR(8), 0xF>(v);
+    v += dpp_f64<DPP_ROW_BCAST15, 0xA>(v);
+    v += dpp_f64<DPP_ROW_BCAST31, 0xC>(v);
+    u64 bits = (u64)__double_as_longlong(v);
+    u32 lo = (u32)__builtin_amdgcn_readlane((int)(u32)bits, 63);
+    u32 hi = (u32)__builtin_amdgcn_readlane((int)(u32)(bits >> 32), 63);
+    return __longlong_as_double((long long)(((u64)hi << 32) | lo));
+}
+
+__device__ __forceinline__ u32 lane_id() { return threadIdx.x & (WAVE - 1); }
+
+// ------------------------------------------------------------------------------------------
+// geometry helpers
+// ------------------------------------------------------------------------------------------
+// Largest b with first_seq[b] <= seq (seq < n_pkts).
+__device__ __forceinline__ u32 find_bucket(const u32* __restrict__ fs, u32 B, u32 seq) {
+    u32 lo = 0, hi = B;
+    while (hi - lo > 1) {
+        u32 mid = (lo + hi) >> 1;
+        if (fs[mid] <= seq) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// First element and float count of packet `seq`, which lies in bucket b.
+__device__ __forceinline__ void packet_span(const Geo& g, u32 seq, u32 b, u64* elem, u32* len) {
+    u64 start = (u64)(seq - g.first_seq[b]) * g.P;
+    u64 left = g.b_cnt[b] - start;
+    *elem = g.b_off[b] + start;
+    *len = left < g.P ? (u32)left : g.P;
+}
+
+// ------------------------------------------------------------------------------------------
+// small utility kernels
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fill_u64(u64* __restrict__ p, u64 n, u64 v) {
+    u64 stride = (u64)gridDim.x * blockDim.x;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
+}
+
+__global__ void reset_counters(u64* __restrict__ c, int keep_round_totals) {
+    u32 t = threadIdx.x;
+    if (t >= C_COUNT) return;
+    if (t == C_LO) c[t] = NONE64;
+    else if (t == C_HI) c[t] = 0;
+    else if (!keep_round_totals) c[t] = 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// sender: gradient -> wire packets
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void packetize_kernel(Geo g, u32 w, u32 round, const float* __restrict__ grad,
+                                                        u64 elem_base, u32 first_seq, u32 n, const u32* __restrict__ slot_map,
+                                                        u64 slot_base, u64 n_slots, uint8_t* __restrict__ packets,
+                                                        uint16_t* __restrict__ src_worker, u64* __restrict__ counters) {
+    u32 lane = lane_id();
+    u32 wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    u32 n_waves = gridDim.x * blockDim.x / WAVE;
+    for (u32 i = wave; i < n; i += n_waves) {
+        u32 seq = first_seq + i;
+        u64 slot = slot_map ? (u64)slot_map[i] : slot_base + i;
+        if (slot >= n_slots) {
+            if (lane == 0) atomicAdd(&counters[C_PKT_BAD], 1ull);
+            continue;
+        }
+        u32 b = find_bucket(g.first_seq, g.B, seq);
+        u64 elem; u32 len;
+        packet_span(g, seq, b, &elem, &len);
+        const float* src = grad + (elem - elem_base);
+        uint4* dst = (uint4*)(packets + slot * g.stride);
+        for (u32 u = lane; u < g.units; u += WAVE) {
+            u32 q[4];
+            #pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                u32 i4 = 4 * u + c;           // float position inside the packet; 0,1 = header
+                if (i4 == 0) q[c] = seq;
+                else if (i4 == 1) q[c] = (round & 0xFFFFu) | (len << 16);
+                else q[c] = (i4 - 2 < len) ? __float_as_uint(src[i4 - 2]) : 0u;
+            }
+            dst[u] = make_uint4(q[0], q[1], q[2], q[3]);
+        }
+        if (lane == 0) src_worker[slot] = (uint16_t)w;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// receiver step 1: index the arrivals
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __restrict__ packets,
+                                                      const uint16_t* __restrict__ src_worker, u64 n_slots,
+                                                      const u64* __restrict__ mask, const u32* __restrict__ order,
+                                                      u64 n_arrivals, u32 cur_round, const u64* __restrict__ bitmap,
+                                                      u64* __restrict__ pending, u64* __restrict__ counters) {
+    u64 k = (u64)blockIdx.x * blockDim.x + threadIdx.x;
+    enum { LOST = 0, STALE, INVALID, DUP, CAND };
+    int cls = LOST;
+    u32 seq_lo = 0xFFFFFFFFu, seq_hi = 0;
+    if (k < n_arrivals) {
+        u64 slot = order ? (u64)order[k] : k;
+        if (slot >= n_slots) {
+            cls = INVALID;
+        } else if (mask && !((mask[slot >> 6] >> (slot & 63)) & 1ull)) {
+            cls = LOST;                                        // never looked at
+        } else {
+            uint2 hdr = *(const uint2*)(packets + slot * g.stride);
+            u32 seq = hdr.x, round = hdr.y & 0xFFFFu, len = hdr.y >> 16;
+            u32 w = src_worker[slot];
+            if (round != cur_round) {
+                cls = STALE;
+            } else if (w >= g.W || seq >= g.n_pkts) {
+                cls = INVALID;
+            } else {
+                u32 b = find_bucket(g.first_seq, g.B, seq);
+                u64 elem; u32 want;
+                packet_span(g, seq, b, &elem, &want);
+                if (len != want) {
+                    cls = INVALID;
+                } else if ((bitmap[(u64)w * g.words_pw + (seq >> 6)] >> (seq & 63)) & 1ull) {
+                    cls = DUP;                                 // delivered by an earlier batch
+                } else {
+                    cls = CAND;
+                    atomicMin(&pending[(u64)w * g.n_pkts + seq], (k << 32) | slot);
+                    seq_lo = seq; seq_hi = seq + 1;
+                }
+            }
+        }
+    }
+    // one atomic per wave and class
+    u64 m_stale = __ballot(cls == STALE), m_inv = __ballot(cls == INVALID);
+    u64 m_dup = __ballot(cls == DUP), m_cand = __ballot(cls == CAND);
+    u32 lo = wave_reduce<OpMin>(seq_lo), hi = wave_reduce<OpMax>(seq_hi);
+    if (lane_id() == 0) {
+        if (m_stale) atomicAdd(&counters[C_STALE], (u64)__popcll(m_stale));
+        if (m_inv) atomicAdd(&counters[C_INVALID], (u64)__popcll(m_inv));
+        if (m_dup) atomicAdd(&counters[C_DUP_PREV], (u64)__popcll(m_dup));
+        if (m_cand) {
+            atomicAdd(&counters[C_CANDIDATES], (u64)__popcll(m_cand));
+            atomicMin(&counters[C_LO], (u64)lo);
+            atomicMax(&counters[C_HI], (u64)hi);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// receiver step 2: gather payloads per output packet and accumulate
+// ------------------------------------------------------------------------------------------
+#define GROUP 8   // payload loads kept in flight per lane
+
+// Sum the payload unit `u` (16 bytes at offset 16u of each packet) over the workers in `sub`
+// (bit w set = worker w delivered this packet in this batch), ascending worker order.
+__device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, u32 stride, u32 u, bool active,
+                                           u64 sub, u32 slot32, u32 lane_base) {
+    float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+    while (sub) {
+        float4 v[GROUP];
+        #pragma unroll
+        for (int j = 0; j < GROUP; ++j) {
+            v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (sub) {
+                u32 w = (u32)__builtin_ctzll(sub);
+                sub &= sub - 1;
+                u32 slot = (u32)__builtin_amdgcn_readlane((int)slot32, (int)(lane_base + w));
+                if (active) v[j] = *(const float4*)(packets + (u64)slot * stride + 16ull * u);
+            }
+        }
+        #pragma unroll
+        for (int j = 0; j < GROUP; ++j) { a.x += v[j].x; a.y += v[j].y; a.z += v[j].z; a.w += v[j].w; }
+    }
+    return a;
+}
+
+__global__ __launch_bounds__(256) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
+                                                         u64* __restrict__ pending, u64* __restrict__ bitmap,
+                                                         float* __restrict__ acc, u64* __restrict__ counters) {
+    const u64 lo = counters[C_LO], hi = counters[C_HI];
+    if (hi == 0) return;                                    // no candidate in this batch
+    const u32 lane = lane_id();
+    const u32 wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const u32 n_waves = gridDim.x * blockDim.x / WAVE;
+    const u32 run = g.run, W = g.W;
+    const u32 r_lane = lane / W, w_lane = lane - r_lane * W;
+    const bool lane_used = lane < run * W;
+    const u64 wmask = (W == 64) ? NONE64 : ((1ull << W) - 1);
+    const u32 first_run = (u32)(lo / run), end_run = (u32)((hi + run - 1) / run);
+    u32 accepted = 0;
+
+    for (u32 rn = first_run + wave; rn < end_run; rn += n_waves) {
+        const u32 seq0 = rn * run;
+        const u32 seq_l = seq0 + r_lane;
+        const bool valid = lane_used && seq_l < g.n_pkts;
+        u64 p = NONE64, word = 0;
+        if (valid) {
+            p = pending[(u64)w_lane * g.n_pkts + seq_l];
+            word = bitmap[(u64)w_lane * g.words_pw + (seq_l >> 6)];
+        }
+        const bool has = p != NONE64;
+        const u64 hasmask = __ballot(has);
+        if (!hasmask) continue;
+        const u64 oldmask = __ballot((word >> (seq_l & 63)) & 1ull);
+        if (has) {
+            pending[(u64)w_lane * g.n_pkts + seq_l] = NONE64;          // leave the index empty for the next batch
+            atomicOr(&bitmap[(u64)w_lane * g.words_pw + (seq_l >> 6)], 1ull << (seq_l & 63));
+        }
+        accepted += (u32)__popcll(hasmask);
+        const u32 slot32 = (u32)p;
+
+        for (u32 r = 0; r < run; ++r) {
+            const u64 sub = (hasmask >> (r * W)) & wmask;
+            if (!sub) continue;
+            const bool rmw = ((oldmask >> (r * W)) & wmask) != 0;      // span already holds earlier arrivals
+            const u32 seq = seq0 + r;
+            const u32 b = find_bucket(g.first_seq, g.B, seq);
+            u64 elem; u32 len;
+            packet_span(g, seq, b, &elem, &len);
+            const u32 units = (len + 2 + 3) >> 2;                        // 16-byte units holding header + payload
+            float* dst0 = acc + elem - 2;                                // float position i of the packet -> dst0[i]
+            for (u32 u0 = 0; u0 < units; u0 += WAVE) {
+                const u32 u = u0 + lane;
+                const bool active = u < units;
+                float4 a = sum_unit(packets, g.stride, u, active, sub, slot32, r * W);
+                if (active) {
+                    float q[4] = {a.x, a.y, a.z, a.w};
+                    #pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        u32 i4 = 4 * u + c;
+                        if (i4 >= 2 && i4 - 2 < len) {
+                            float* d = dst0 + i4;
+                            *d = rmw ? (*d + q[c]) : q[c];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    if (lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
+}
+
+// ------------------------------------------------------------------------------------------
+// probe: per-(worker,bucket) loss count, prefix of list lengths, ordered list
+// ------------------------------------------------------------------------------------------
+// Bits of word index `wd` that belong to sequence range [s0, s1).
+__device__ __forceinline__ u64 range_mask(u32 wd, u32 s0, u32 s1) {
+    u64 m = NONE64;
+    u64 base = (u64)wd * 64;
+    if (base < s0) m &= NONE64 << (s0 - base);
+    if (base + 64 > s1) m &= NONE64 >> (base + 64 - s1);
+    return m;
+}
+
+__global__ __launch_bounds__(256) void loss_count(Geo g, const u64* __restrict__ bitmap, u32 bound_ppm,
+                                                  u32* __restrict__ missing_out, u32* __restrict__ need) {
+    const u32 lane = lane_id();
+    const u32 wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const u32 n_waves = gridDim.x * blockDim.x / WAVE;
+    const u32 pairs = g.W * g.B;
+    for (u32 pr = wave; pr < pairs; pr += n_waves) {
+        const u32 w = pr / g.B, b = pr - w * g.B;
+        const u32 s0 = g.first_seq[b], s1 = g.first_seq[b + 1];
+        const u32 wd0 = s0 >> 6, wd1 = (s1 - 1) >> 6;
+        u32 cnt = 0;
+        for (u32 wd = wd0 + lane; wd <= wd1; wd += WAVE)
+            cnt += (u32)__popcll(bitmap[(u64)w * g.words_pw + wd] & range_mask(wd, s0, s1));
+        const u32 got = wave_reduce<OpAdd>(cnt);
+        if (lane == 0) {
+            const u32 n_b = s1 - s0;
+            const u32 miss = n_b - got;
+            const u64 allowed = ((u64)bound_ppm * n_b) / 1000000ull;
+            if (missing_out) missing_out[pr] = miss;
+            need[pr] = (u64)miss > allowed ? miss : 0u;
+        }
+    }
+}
+
+// Exclusive prefix of need[0..n) into offs[0..n); total list length to *total (device) and to
+// the host mailbox.  Single block of 1024 threads.
+__global__ __launch_bounds__(1024) void scan_need(const u32* __restrict__ need, u32 n, u64* __restrict__ offs,
+                                                  u64* __restrict__ mailbox) {
+    __shared__ u64 part[1024];
+    const u32 t = threadIdx.x;
+    const u32 per = (n + 1023) / 1024;
+    const u32 i0 = t * per, i1 = min(n, i0 + per);
+    u64 s = 0;
+    for (u32 i = i0; i < i1; ++i) s += need[i];
+    part[t] = s;
+    __syncthreads();
+    for (u32 d = 1; d < 1024; d <<= 1) {
+        u64 v = t >= d ? part[t - d] : 0;
+        __syncthreads();
+        part[t] += v;
+        __syncthreads();
+    }
+    u64 run = part[t] - s;     // exclusive prefix of this thread's chunk
+    for (u32 i = i0; i < i1; ++i) { offs[i] = run; run += need[i]; }
+    if (t == 1023) mailbox[0] = part[1023];
+}
+
+__global__ __launch_bounds__(256) void emit_retx(Geo g, const u64* __restrict__ bitmap, const u32* __restrict__ need,
+                                                 const u64* __restrict__ offs, u64* __restrict__ list, u64 capacity) {
+    const u32 lane = lane_id();
+    const u32 wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const u32 n_waves = gridDim.x * blockDim.x / WAVE;
+    const u32 pairs = g.W * g.B;
+    for (u32 pr = wave; pr < pairs; pr += n_waves) {
+        if (need[pr] == 0) continue;
+        const u32 w = pr / g.B, b = pr - w * g.B;
+        const u32 s0 = g.first_seq[b], s1 = g.first_seq[b + 1];
+        const u32 wd0 = s0 >> 6, wd1 = (s1 - 1) >> 6;
+        u64 base = offs[pr];
+        for (u32 c0 = wd0; c0 <= wd1; c0 += WAVE) {
+            const u32 wd = c0 + lane;
+            u64 m = 0;
+            if (wd <= wd1) m = ~bitmap[(u64)w * g.words_pw + wd] & range_mask(wd, s0, s1);
+            const u32 c = (u32)__popcll(m);
+            const u32 incl = wave_scan_incl<OpAdd>(c);
+            const u32 total = (u32)__builtin_amdgcn_readlane((int)incl, 63);
+            u64 pos = base + (incl - c);
+            while (m) {
+                const u32 bit = (u32)__builtin_ctzll(m);
+                m &= m - 1;
+                if (pos < capacity) list[pos] = ((u64)w << 32) | ((u64)wd * 64 + bit);
+                ++pos;
+            }
+            base += total;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// finalize (zero-fill + mean over all W) with fused partial sums of squares; norm reduction
+// ------------------------------------------------------------------------------------------
+#define FIN_TILE 8   // consecutive packets per wave step; divides 64 so a tile sits in one bitmap word
+
+__global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restrict__ bitmap, const float* __restrict__ acc,
+                                                     float* __restrict__ out, float inv_w, int use_div, float wf,
+                                                     double* __restrict__ partials) {
+    __shared__ double wsum[4];
+    const u32 lane = lane_id();
+    const u32 wave_in_block = threadIdx.x / WAVE;
+    const u32 wave = blockIdx.x * (blockDim.x / WAVE) + wave_in_block;
+    const u32 n_waves = gridDim.x * (blockDim.x / WAVE);
+    const u32 n_tiles = (g.n_pkts + FIN_TILE - 1) / FIN_TILE;
+    double dsum = 0.0;
+    for (u32 tile = wave; tile < n_tiles; tile += n_waves) {
+        const u32 seq0 = tile * FIN_TILE;
+        u64 any = 0;
+        for (u32 w = 0; w < g.W; ++w) any |= bitmap[(u64)w * g.words_pw + (seq0 >> 6)];
+        any >>= (seq0 & 63);
+        u32 b = find_bucket(g.first_seq, g.B, seq0);
+        for (u32 t = 0; t < FIN_TILE; ++t) {
+            const u32 seq = seq0 + t;
+            if (seq >= g.n_pkts) break;
+            while (seq >= g.first_seq[b + 1]) ++b;
+            u64 elem; u32 len;
+            packet_span(g, seq, b, &elem, &len);
+            float s = 0.f;
+            if ((any >> t) & 1ull) {
+                for (u32 j = lane; j < len; j += WAVE) {
+                    float v = acc[elem + j];
+                    v = use_div ? v / wf : v * inv_w;
+                    out[elem + j] = v;
+                    s += v * v;
+                }
+            } else {
+                for (u32 j = lane; j < len; j += WAVE) out[elem + j] = 0.f;   // never received: exactly zero
+            }
+            dsum += (double)s;
+        }
+    }
+    dsum = wave_sum_f64(dsum);
+    if (lane == 0) wsum[wave_in_block] = dsum;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+// Sum of squares of a plain vector (16-byte aligned), same partials layout.
+__global__ __launch_bounds__(256) void sumsq_vec(const float* __restrict__ v, u64 n, double* __restrict__ partials) {
+    __shared__ double wsum[4];
+    const u64 n4 = n / 4;
+    const float4* v4 = (const float4*)v;
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    double dsum = 0.0;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+        float4 x = v4[i];
+        dsum += (double)((x.x * x.x + x.y * x.y) + (x.z * x.z + x.w * x.w));
+    }
+    if (blockIdx.x == 0 && threadIdx.x < (u32)(n - 4 * n4)) {
+        float x = v[4 * n4 + threadIdx.x];
+        dsum += (double)(x * x);
+    }
+    dsum = wave_sum_f64(dsum);
+    if (lane_id() == 0) wsum[threadIdx.x / WAVE] = dsum;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+// Fixed-order sum of the per-block partials; the result goes to the host mailbox.
+__global__ __launch_bounds__(256) void reduce_partials(const double* __restrict__ partials, u32 n, double* __restrict__ mailbox) {
+    __shared__ double wsum[4];
+    double s = 0.0;
+    for (u32 i = threadIdx.x; i < n; i += 256) s += partials[i];
+    s = wave_sum_f64(s);
+    if (lane_id() == 0) wsum[threadIdx.x / WAVE] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) mailbox[0] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+struct dblp_ctx {
+    Geo g;
+    u64 N;
+    double eta;
+    int device;
+    hipStream_t stream;
+    int n_cus;
+    // device state
+    u32* d_first_seq; u64* d_b_off; u64* d_b_cnt;
+    u64* d_bitmap; u64* d_pending; float* d_acc; u64* d_counters;
+    u32* d_need; u32* d_missing; u64* d_offs; double* d_partials;
+    u64* h_mailbox;         // pinned host memory, 8 x u64, also mapped into the device
+    u64* d_mailbox;         // device address of h_mailbox
+    // host copies of the geometry
+    u32* h_first_seq; u64* h_b_off; u64* h_b_cnt;
+    u32 n_partials;         // blocks of the last finalize / sumsq launch
+    // protocol state
+    int round_open; int finalized; uint16_t round;
+    double prev_norm; int have_prev;
+    char err[256];
+};
+
+static int fail(dblp_ctx* c, int code, const char* what) {
+    if (c) snprintf(c->err, sizeof c->err, "%s", what);
+    return code;
+}
+
+static int fail_hip(dblp_ctx* c, hipError_t e, const char* what) {
+    if (c) snprintf(c->err, sizeof c->err, "%s: %s", what, hipGetErrorString(e));
+    return DBLP_EHIP;
+}
+
+#define HIP_TRY(c, call)                                            \
+    do {                                                            \
+        hipError_t e__ = (call);                                    \
+        if (e__ != hipSuccess) return fail_hip((c), e__, #call);    \
+    } while (0)
+
+#define LAUNCH_CHECK(c, name)                                       \
+    do {                                                            \
+        hipError_t e__ = hipGetLastError();                         \
+        if (e__ != hipSuccess) return fail_hip((c), e__, name);     \
+    } while (0)
+
+static u32 grid_for(const dblp_ctx* c, u64 blocks_wanted, u32 blocks_per_cu) {
+    u64 cap = (u64)c->n_cus * blocks_per_cu;
+    u64 g = blocks_wanted < cap ? blocks_wanted : cap;
+    return (u32)(g ? g : 1);
+}
+
+extern "C" const char* dblp_last_error(const dblp_ctx* ctx) { return ctx ? ctx->err : "null context"; }
+
+extern "C" int dblp_destroy(dblp_ctx* c) {
+    if (!c) return DBLP_OK;
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    void* dev[] = {c->d_first_seq, c->d_b_off, c->d_b_cnt, c->d_bitmap, c->d_pending, c->d_acc,
+                   c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials};
+    for (void* p : dev) if (p) (void)hipFree(p);
+    if (c->h_mailbox) (void)hipHostFree(c->h_mailbox);
+    free(c->h_first_seq); free(c->h_b_off); free(c->h_b_cnt);
+    free(c);
+    return DBLP_OK;
+}
+
+#define FIN_BLOCKS_PER_CU 8
+
+extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
+    if (!out || !cfg || !cfg->buckets) return DBLP_EINVAL;
+    if (cfg->n_workers == 0 || cfg->n_workers > DBLP_MAX_WORKERS) return DBLP_EINVAL;
+    if (cfg->payload_floats == 0 || cfg->payload_floats > 65535) return DBLP_EINVAL;
+    if (cfg->n_buckets == 0 || cfg->n_elems == 0) return DBLP_EINVAL;
+    if (!(cfg->eta >= 0.0)) return DBLP_EINVAL;
+    const u32 B = cfg->n_buckets, P = cfg->payload_floats;
+    u64 expect = 0, n_pkts = 0;
+    for (u32 b = 0; b < B; ++b) {
+        if (cfg->buckets[b].elem_offset != expect) return DBLP_EINVAL;
+        if (cfg->buckets[b].elem_count == 0 || cfg->buckets[b].elem_count >= (1ull << 32)) return DBLP_EINVAL;
+        expect += cfg->buckets[b].elem_count;
+        n_pkts += (cfg->buckets[b].elem_count + P - 1) / P;
+    }
+    if (expect != cfg->n_elems) return DBLP_EINVAL;
+    if (n_pkts >= 0xFFFFFFFFull) return DBLP_EINVAL;
+
+    dblp_ctx* c = (dblp_ctx*)calloc(1, sizeof *c);
+    if (!c) return DBLP_ENOMEM;
+    c->N = cfg->n_elems; c->eta = cfg->eta; c->device = cfg->device; c->stream = (hipStream_t)cfg->stream;
+    c->h_first_seq = (u32*)malloc((B + 1) * sizeof(u32));
+    c->h_b_off = (u64*)malloc(B * sizeof(u64));
+    c->h_b_cnt = (u64*)malloc(B * sizeof(u64));
+    if (!c->h_first_seq || !c->h_b_off || !c->h_b_cnt) { dblp_destroy(c); return DBLP_ENOMEM; }
+    u64 seq = 0;
+    for (u32 b = 0; b < B; ++b) {
+        c->h_first_seq[b] = (u32)seq;
+        c->h_b_off[b] = cfg->buckets[b].elem_offset;
+        c->h_b_cnt[b] = cfg->buckets[b].elem_count;
+        seq += (c->h_b_cnt[b] + P - 1) / P;
+    }
+    c->h_first_seq[B] = (u32)seq;
+
+    Geo& g = c->g;
+    g.B = B; g.P = P; g.W = cfg->n_workers; g.n_pkts = (u32)n_pkts;
+    g.stride = (8 + 4 * P + 15) / 16 * 16;
+    g.units = g.stride / 16;
+    g.run = 64 / g.W ? 64 / g.W : 1;
+    g.words_pw = (n_pkts + 63) / 64;
+
+    hipError_t e = hipSetDevice(c->device);
+    if (e != hipSuccess) { dblp_destroy(c); return DBLP_EHIP; }
+    hipDeviceProp_t prop;
+    e = hipGetDeviceProperties(&prop, c->device);
+    if (e != hipSuccess) { dblp_destroy(c); return DBLP_EHIP; }
+    c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+
+    const u64 pairs = (u64)g.W * B;
+    const u32 max_partials = (u32)c->n_cus * FIN_BLOCKS_PER_CU;
+    bool ok = true;
+    ok = ok && hipMalloc(&c->d_first_seq, (B + 1) * sizeof(u32)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_b_off, B * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_b_cnt, B * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_bitmap, g.W * g.words_pw * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_pending, (u64)g.W * n_pkts * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_acc, c->N * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_counters, C_COUNT * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_need, pairs * sizeof(u32)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_missing, pairs * sizeof(u32)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_offs, pairs * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_partials, max_partials * sizeof(double)) == hipSuccess;
+    ok = ok && hipHostMalloc((void**)&c->h_mailbox, 8 * sizeof(u64), hipHostMallocMapped) == hipSuccess;
+    if (!ok) { (void)hipGetLastError(); dblp_destroy(c); return DBLP_ENOMEM; }
+    ok = ok && hipHostGetDevicePointer((void**)&c->d_mailbox, c->h_mailbox, 0) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->d_first_seq, c->h_first_seq, (B + 1) * sizeof(u32), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->d_b_off, c->h_b_off, B * sizeof(u64), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->d_b_cnt, c->h_b_cnt, B * sizeof(u64), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    if (!ok) { (void)hipGetLastError(); dblp_destroy(c); return DBLP_EHIP; }
+    g.first_seq = c->d_first_seq; g.b_off = c->d_b_off; g.b_cnt = c->d_b_cnt;
+
+    const u64 n_pending = (u64)g.W * n_pkts;
+    hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n_pending + 255) / 256, 16)), dim3(256), 0, c->stream,
+                       c->d_pending, n_pending, NONE64);
+    hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (g.W * g.words_pw + 255) / 256, 16)), dim3(256), 0, c->stream,
+                       c->d_bitmap, g.W * g.words_pw, 0ull);
+    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters, 0);
+    e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess || hipGetLastError() != hipSuccess) { dblp_destroy(c); return DBLP_EHIP; }
+    c->err[0] = 0;
+    *out = c;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_layout(const dblp_ctx* c, uint64_t* n_pkts, uint32_t* stride, uint64_t* words_pw) {
+    if (!c) return DBLP_EINVAL;
+    if (n_pkts) *n_pkts = c->g.n_pkts;
+    if (stride) *stride = c->g.stride;
+    if (words_pw) *words_pw = c->g.words_pw;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
+    if (!c) return DBLP_EINVAL;
+    HIP_TRY(c, hipSetDevice(c->device));
+    const u64 n = c->g.W * c->g.words_pw;
+    hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n + 255) / 256, 16)), dim3(256), 0, c->stream, c->d_bitmap, n, 0ull);
+    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters, 0);
+    LAUNCH_CHECK(c, "begin_round");
+    c->round = round; c->round_open = 1; c->finalized = 0;
+    return DBLP_OK;
+}
+
+// Element window [lo, hi) covered by packets first_seq .. first_seq + n - 1 (host geometry).
+static void seq_window(const dblp_ctx* c, u64 first_seq, u64 n, u64* lo, u64* hi) {
+    const Geo& g = c->g;
+    auto span = [&](u64 seq, u64* elem, u64* len) {
+        u32 a = 0, b = g.B;
+        while (b - a > 1) { u32 m = (a + b) / 2; if (c->h_first_seq[m] <= seq) a = m; else b = m; }
+        u64 start = (seq - c->h_first_seq[a]) * g.P;
+        u64 left = c->h_b_cnt[a] - start;
+        *elem = c->h_b_off[a] + start;
+        *len = left < g.P ? left : g.P;
+    };
+    u64 e0, l0, e1, l1;
+    span(first_seq, &e0, &l0);
+    span(first_seq + n - 1, &e1, &l1);
+    *lo = e0; *hi = e1 + l1;
+}
+
+extern "C" int dblp_packetize(dblp_ctx* c, uint32_t w, uint16_t round, const float* d_grad, uint64_t elem_base,
+                              uint64_t n_grad, uint64_t first_seq, uint64_t n_pkts, const uint32_t* d_slot_map,
+                              uint64_t slot_base, uint64_t n_slots, void* d_packets, uint16_t* d_src_worker) {
+    if (!c) return DBLP_EINVAL;
+    if (n_pkts == 0) return DBLP_OK;
+    if (!d_grad || !d_packets || !d_src_worker) return fail(c, DBLP_EINVAL, "packetize: null pointer");
+    if (w >= c->g.W) return fail(c, DBLP_EINVAL, "packetize: worker out of range");
+    if (first_seq >= c->g.n_pkts || n_pkts > c->g.n_pkts - first_seq) return fail(c, DBLP_EINVAL, "packetize: seq range");
+    if (((uintptr_t)d_packets & 15) != 0) return fail(c, DBLP_EINVAL, "packetize: d_packets must be 16-byte aligned");
+    if (!d_slot_map && (slot_base > n_slots || n_pkts > n_slots - slot_base)) return fail(c, DBLP_EINVAL, "packetize: slots exceed buffer");
+    u64 lo, hi;
+    seq_window(c, first_seq, n_pkts, &lo, &hi);
+    if (lo < elem_base || hi > elem_base + n_grad) return fail(c, DBLP_EINVAL, "packetize: packets outside the gradient window");
+    HIP_TRY(c, hipSetDevice(c->device));
+    hipLaunchKernelGGL(packetize_kernel, dim3(grid_for(c, (n_pkts + 3) / 4, 16)), dim3(256), 0, c->stream, c->g, w,
+                       (u32)round, d_grad, (u64)elem_base, (u32)first_seq, (u32)n_pkts, d_slot_map, (u64)slot_base,
+                       (u64)n_slots, (uint8_t*)d_packets, d_src_worker, c->d_counters);
+    LAUNCH_CHECK(c, "packetize");
+    if (d_slot_map) {   // slots come from device memory: the kernel checks them, report here
+        u64 bad = 0;
+        HIP_TRY(c, hipMemcpyAsync(c->h_mailbox + 4, c->d_counters + C_PKT_BAD, sizeof(u64), hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        bad = c->h_mailbox[4];
+        if (bad) {
+            HIP_TRY(c, hipMemsetAsync(c->d_counters + C_PKT_BAD, 0, sizeof(u64), c->stream));
+            return fail(c, DBLP_EINVAL, "packetize: slot map entry outside the packet buffer");
+        }
+    }
+    return DBLP_OK;
+}
+
+extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uint16_t* d_src_worker, uint64_t n_slots,
+                                   const uint64_t* d_mask, const uint32_t* d_order, uint64_t n_arrivals) {
+    if (!c) return DBLP_EINVAL;
+    if (!c->round_open) return fail(c, DBLP_ESTATE, "apply_arrivals before begin_round");
+    if (n_arrivals == 0) return DBLP_OK;
+    if (!d_packets || !d_src_worker) return fail(c, DBLP_EINVAL, "apply_arrivals: null pointer");
+    if (((uintptr_t)d_packets & 15) != 0) return fail(c, DBLP_EINVAL, "apply_arrivals: d_packets must be 16-byte aligned");
+    if (n_slots >= 0xFFFFFFFFull || n_arrivals >= 0xFFFFFFFFull) return fail(c, DBLP_EINVAL, "apply_arrivals: too many slots");
+    if (!d_order && n_arrivals > n_slots) return fail(c, DBLP_EINVAL, "apply_arrivals: identity order longer than the buffer");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const Geo& g = c->g;
+    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters, 1);
+    hipLaunchKernelGGL(index_arrivals, dim3((u32)((n_arrivals + 255) / 256)), dim3(256), 0, c->stream, g,
+                       (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
+                       (u64)n_arrivals, (u32)c->round, c->d_bitmap, c->d_pending, c->d_counters);
+    const u64 runs = ((u64)g.n_pkts + g.run - 1) / g.run;
+    hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, (runs + 3) / 4, 8)), dim3(256), 0, c->stream, g,
+                       (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc, c->d_counters);
+    LAUNCH_CHECK(c, "apply_arrivals");
+    c->finalized = 0;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_loss_account(dblp_ctx* c, uint32_t bound_ppm, uint32_t* d_missing, uint64_t* d_retx_list,
+                                 uint64_t retx_capacity, uint64_t* h_retx_count, int* h_all_met) {
+    if (!c) return DBLP_EINVAL;
+    if (!c->round_open) return fail(c, DBLP_ESTATE, "loss_account before begin_round");
+    if (!h_retx_count || !h_all_met) return fail(c, DBLP_EINVAL, "loss_account: null host pointer");
+    if (!d_retx_list && retx_capacity) return fail(c, DBLP_EINVAL, "loss_account: null list with capacity");
+    if (bound_ppm > 1000000u) return fail(c, DBLP_EINVAL, "loss_account: bound above 100%");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const Geo& g = c->g;
+    const u32 pairs = g.W * g.B;
+    hipLaunchKernelGGL(loss_count, dim3(grid_for(c, (pairs + 3) / 4, 8)), dim3(256), 0, c->stream, g, c->d_bitmap,
+                       bound_ppm, d_missing ? d_missing : c->d_missing, c->d_need);
+    hipLaunchKernelGGL(scan_need, dim3(1), dim3(1024), 0, c->stream, c->d_need, pairs, c->d_offs, c->d_mailbox);
+    if (retx_capacity)
+        hipLaunchKernelGGL(emit_retx, dim3(grid_for(c, (pairs + 3) / 4, 8)), dim3(256), 0, c->stream, g, c->d_bitmap,
+                           c->d_need, c->d_offs, (u64*)d_retx_list, (u64)retx_capacity);
+    LAUNCH_CHECK(c, "loss_account");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    const u64 total = c->h_mailbox[0];
+    *h_retx_count = total;
+    *h_all_met = total == 0;
+    if (total > retx_capacity) return fail(c, DBLP_ECAPACITY, "retransmit list truncated");
+    return DBLP_OK;
+}
+
+extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
+    if (!c) return DBLP_EINVAL;
+    if (!c->round_open) return fail(c, DBLP_ESTATE, "finalize before begin_round");
+    if (compensation != DBLP_COMP_ZEROFILL_MEAN) return fail(c, DBLP_EINVAL, "finalize: unknown compensation mode");
+    if (!d_out) return fail(c, DBLP_EINVAL, "finalize: null output");
+    HIP_TRY(c, hipSetDevice(c->device));
+    const Geo& g = c->g;
+    const u32 W = g.W;
+    const int pow2 = (W & (W - 1)) == 0;
+    const u64 tiles = ((u64)g.n_pkts + FIN_TILE - 1) / FIN_TILE;
+    const u32 grid = grid_for(c, (tiles + 3) / 4, FIN_BLOCKS_PER_CU);
+    hipLaunchKernelGGL(finalize_mean, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc, d_out,
+                       1.0f / (float)W, !pow2, (float)W, c->d_partials);
+    LAUNCH_CHECK(c, "finalize");
+    c->n_partials = grid;
+    c->finalized = 1;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_phase_signal(dblp_ctx* c, const float* d_vec, double* h_norm, double* h_rel_delta, int* h_critical) {
+    if (!c) return DBLP_EINVAL;
+    if (!h_norm || !h_rel_delta || !h_critical) return fail(c, DBLP_EINVAL, "phase_signal: null host pointer");
+    HIP_TRY(c, hipSetDevice(c->device));
+    u32 n_partials;
+    if (d_vec) {
+        if (((uintptr_t)d_vec & 15) != 0) return fail(c, DBLP_EINVAL, "phase_signal: d_vec must be 16-byte aligned");
+        n_partials = grid_for(c, (c->N / 4 + 255) / 256, FIN_BLOCKS_PER_CU);
+        hipLaunchKernelGGL(sumsq_vec, dim3(n_partials), dim3(256), 0, c->stream, d_vec, (u64)c->N, c->d_partials);
+        c->finalized = 0;   // the partials no longer belong to a finalize
+    } else {
+        if (!c->finalized) return fail(c, DBLP_ESTATE, "phase_signal without a finalize in this round");
+        n_partials = c->n_partials;
+    }
+    hipLaunchKernelGGL(reduce_partials, dim3(1), dim3(256), 0, c->stream, c->d_partials, n_partials,
+                       (double*)(c->d_mailbox + 1));
+    LAUNCH_CHECK(c, "phase_signal");
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    double ss;
+    memcpy(&ss, c->h_mailbox + 1, sizeof ss);
+    const double norm = sqrt(ss);
+    if (!c->have_prev || c->prev_norm == 0.0) {
+        *h_rel_delta = INFINITY;
+        *h_critical = 1;
+    } else {
+        *h_rel_delta = fabs(c->prev_norm - norm) / c->prev_norm;
+        *h_critical = *h_rel_delta >= c->eta;
+    }
+    *h_norm = norm;
+    c->prev_norm = norm;
+    c->have_prev = 1;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_get_bitmap(dblp_ctx* c, uint64_t* d_out) {
+    if (!c || !d_out) return DBLP_EINVAL;
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, hipMemcpyAsync(d_out, c->d_bitmap, c->g.W * c->g.words_pw * sizeof(u64), hipMemcpyDeviceToDevice, c->stream));
+    return DBLP_OK;
+}
+
+extern "C" int dblp_get_counters(dblp_ctx* c, uint64_t h[4]) {
+    if (!c || !h) return DBLP_EINVAL;
+    HIP_TRY(c, hipSetDevice(c->device));
+    u64 tmp[C_COUNT];
+    HIP_TRY(c, hipMemcpyAsync(tmp, c->d_counters, sizeof tmp, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    h[0] = tmp[C_ACCEPTED];
+    h[1] = tmp[C_DUP_PREV] + (tmp[C_CANDIDATES] - tmp[C_ACCEPTED]);   // earlier batches + second copies in a batch
+    h[2] = tmp[C_STALE];
+    h[3] = tmp[C_INVALID];
+    return DBLP_OK;
+}
+
+extern "C" int dblp_set_prev_norm(dblp_ctx* c, double norm, int have) {
+    if (!c || !(norm >= 0.0)) return DBLP_EINVAL;
+    c->prev_norm = norm; c->have_prev = have != 0;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_get_prev_norm(const dblp_ctx* c, double* h_norm, int* h_have) {
+    if (!c || !h_norm || !h_have) return DBLP_EINVAL;
+    *h_norm = c->prev_norm; *h_have = c->have_prev;
+    return DBLP_OK;
+}
+
+extern "C" uint32_t dblp_policy_two_level(int critical, uint32_t p_low_ppm, uint32_t p_high_ppm) {
+    return critical ? p_low_ppm : p_high_ppm;
+}
+
+extern "C" uint32_t dblp_policy_three_level(double rel_delta, double eta, uint32_t tight_ppm, uint32_t mid_ppm,
+                                            uint32_t loose_ppm) {
+    if (rel_delta >= eta) return tight_ppm;
+    return rel_delta >= 0.5 * eta ? mid_ppm : loose_ppm;
+}
+
+extern "C" uint32_t dblp_policy_linear(double rel_delta, double eta, uint32_t lo_ppm, uint32_t hi_ppm) {
+    double x = rel_delta / eta;
+    if (!(x < 1.0)) x = 1.0;
+    const double ppm = (double)hi_ppm - ((double)hi_ppm - (double)lo_ppm) * x;
+    return (uint32_t)(floor(ppm / 1000.0 + 0.5)) * 1000u;
+}

@@ -157,3 +157,132 @@ def definition_mean(sc: Scenario, received: np.ndarray) -> np.ndarray:
     for w in range(L.W):
         out += received[w, pkt_of_elem].astype(np.float64) * sc.grad(w).astype(np.float64)
     return out / L.W
+
+
+# ---------------------------------------------------------------------------------------
+# GPU adapter (C-ABI library through its Python binding)
+# ---------------------------------------------------------------------------------------
+def _dev(a: np.ndarray, as_dtype):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a).view(as_dtype)).cuda()
+
+
+class GpuRx:
+    """Drives the HIP library on device-resident packets built by its own packetize."""
+
+    def __init__(self, sc: Scenario, eta: float = 0.5):
+        import torch
+        import paper_2605_01989_amd as dblp
+        L = sc.L
+        self.sc, self.torch = sc, torch
+        self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, eta)
+        assert (self.agg.n_pkts, self.agg.stride) == (L.n_pkts, L.stride)
+        n_slots = L.W * L.n_pkts
+        self.packets = torch.zeros(n_slots * L.stride, dtype=torch.uint8, device="cuda")
+        self.src = torch.full((n_slots,), -1, dtype=torch.int16, device="cuda")
+        self.d_missing = torch.empty(L.W * L.B, dtype=torch.int32, device="cuda")
+        self.d_list = torch.empty(max(n_slots, 1), dtype=torch.int64, device="cuda")
+        self.d_out = torch.empty(L.N, dtype=torch.float32, device="cuda")
+        self.d_bitmap = torch.empty(L.W * self.agg.words_pw, dtype=torch.int64, device="cuda")
+
+    def packetize_all(self, rnd_id: int | None = None):
+        sc, L = self.sc, self.sc.L
+        rnd_id = sc.rnd_id if rnd_id is None else rnd_id
+        for w in range(L.W):
+            d_grad = self.torch.from_numpy(sc.grad(w)).cuda()
+            d_map = _dev(sc.slot_of[w], np.int32)
+            self.agg.packetize(w, rnd_id, d_grad, 0, 0, L.n_pkts, self.packets, self.src, d_slot_map=d_map)
+
+    def upload_packets(self, packets: np.ndarray, src: np.ndarray):
+        """Use host-built wire bytes (e.g. with hand-corrupted headers) instead of packetize."""
+        self.packets.copy_(self.torch.from_numpy(packets))
+        self.src.copy_(self.torch.from_numpy(src.view(np.int16)))
+
+    def begin_round(self, rnd_id):
+        self.agg.begin_round(rnd_id)
+
+    def apply(self, slot_base, n_slots, mask, order, n_arrivals=None):
+        st = self.agg.stride
+        d_mask = None if mask is None else _dev(mask, np.int64)
+        d_order = None if order is None else _dev(np.asarray(order, dtype=np.uint32), np.int32)
+        if order is not None and n_arrivals is None:
+            n_arrivals = int(np.asarray(order).size)
+        if d_order is not None and d_order.numel() == 0:
+            d_order = None
+            n_arrivals = 0
+        self.agg.apply_arrivals(self.packets[slot_base * st:], self.src[slot_base:], n_slots, d_mask, d_order, n_arrivals)
+
+    def loss_account(self, bound_ppm, capacity=None):
+        L = self.sc.L
+        count, met, trunc = self.agg.loss_account(bound_ppm, self.d_missing, self.d_list, capacity)
+        n = min(count, self.d_list.numel() if capacity is None else capacity)
+        missing = self.d_missing.cpu().numpy().view(np.uint32).reshape(L.W, L.B)
+        return missing, self.d_list[:n].cpu().numpy().view(np.uint64), count, met
+
+    def finalize(self):
+        self.agg.finalize(self.d_out)
+        return self.d_out.cpu().numpy()
+
+    def phase_signal(self):
+        return self.agg.phase_signal()
+
+    def bitmap(self):
+        L = self.sc.L
+        self.agg.get_bitmap(self.d_bitmap)
+        words = self.d_bitmap.cpu().numpy().view(np.uint64).reshape(L.W, self.agg.words_pw)
+        bits = np.unpackbits(words.view(np.uint8), axis=1, bitorder="little")
+        assert not bits[:, L.n_pkts:].any(), "bitmap bits set beyond n_pkts"
+        return bits[:, :L.n_pkts]
+
+    def counters(self):
+        return self.agg.get_counters()
+
+
+def abs_scale(sc: Scenario, received: np.ndarray) -> np.ndarray:
+    """(1/W) sum_w received[w, pkt(e)] |g[w, e]|: the natural scale of element e's sum, used as
+    the denominator of the float parity metric (a relative error against the magnitude of the
+    addends, which is what any summation order can guarantee)."""
+    L = sc.L
+    out = np.zeros(L.N, dtype=np.float64)
+    pkt_of_elem = np.empty(L.N, dtype=np.int64)
+    for b in range(L.B):
+        off, cnt = int(L.bucket_off[b]), int(L.bucket_cnt[b])
+        pkt_of_elem[off:off + cnt] = int(L.first_seq[b]) + np.arange(cnt) // L.P
+    for w in range(L.W):
+        out += received[w, pkt_of_elem].astype(np.float64) * np.abs(sc.grad(w).astype(np.float64))
+    return out / L.W
+
+
+FLOAT_TOL = 1e-5   # max relative error of the fp32 aggregate against the fp64 oracle
+
+
+def compare_results(got: dict, ref: dict, sc: Scenario) -> dict:
+    """Integer outputs bit-exact; floats within FLOAT_TOL of the oracle relative to the addends'
+    magnitude; never-received elements exactly zero; norm within 1e-6."""
+    assert np.array_equal(got["bitmap"], ref["bitmap"]), "bitmap differs"
+    assert got["rounds"] == ref["rounds"]
+    assert len(got["probes"]) == len(ref["probes"])
+    for i, (a, b) in enumerate(zip(got["probes"], ref["probes"])):
+        assert a["count"] == b["count"] and a["met"] == b["met"], f"probe {i}: count/met differ"
+        assert np.array_equal(a["missing"], b["missing"]), f"probe {i}: missing counts differ"
+        assert np.array_equal(a["list"], b["list"]), f"probe {i}: retransmit list differs"
+    assert got["counters"] == ref["counters"], (got["counters"], ref["counters"])
+    g, r = got["out"].astype(np.float64), ref["out"]
+    scale = abs_scale(sc, ref["bitmap"])
+    zero = scale == 0
+    assert np.all(g[zero] == 0.0), "element that no worker delivered is not exactly zero"
+    err = np.abs(g - r)
+    rel = float((err[~zero] / scale[~zero]).max()) if (~zero).any() else 0.0
+    assert rel <= FLOAT_TOL, f"float parity {rel:.3e} > {FLOAT_TOL}"
+    nz = r != 0
+    plain = err[nz] / np.abs(r[nz])
+    assert got["critical"] == ref["critical"]
+    if ref["norm"] > 0:
+        assert abs(got["norm"] - ref["norm"]) <= 1e-6 * ref["norm"], (got["norm"], ref["norm"])
+    if np.isfinite(ref["rel_delta"]):
+        assert abs(got["rel_delta"] - ref["rel_delta"]) <= 1e-5
+    else:
+        assert got["rel_delta"] == ref["rel_delta"]
+    return dict(rel_to_addends=rel, rel_to_max=float(err.max() / max(np.abs(r).max(), 1e-300)),
+                plain_rel_max=float(plain.max()) if nz.any() else 0.0,
+                plain_rel_above_tol=int((plain > FLOAT_TOL).sum()), n=int(r.size))

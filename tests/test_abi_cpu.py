@@ -1,0 +1,57 @@
+"""No-GPU checks of the product library: it loads, exports every symbol the header declares,
+and its host-only scalar policies agree with the paper's Table 1 and with the oracle's policies."""
+import math
+import os
+import re
+
+import pytest
+
+import oracle
+import paper_2605_01989_amd as dblp
+from paper_2605_01989_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dblp_agg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dblp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert len(names) >= 15
+    L = dblp.lib()
+    for n in names:
+        assert hasattr(L, n), f"libdblp_agg.so does not export {n}"
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2605_01989_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp", ".c")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in src.replace("no CPU fallback", ""), f"{f} mentions the oracle"
+
+
+def test_two_level_policy_is_table_1():
+    assert dblp.policy_two_level(True, 8000, 408000) == 8000
+    assert dblp.policy_two_level(False, 8000, 408000) == 408000
+    assert dblp.policy_two_level(False, 24000, 424000) == 424000
+
+
+@pytest.mark.parametrize("delta", [0.0, 0.01, 0.1, 0.2499, 0.25, 0.3, 0.4999, 0.5, 0.7, 3.0, math.inf])
+def test_extension_policies_agree_with_oracle(delta):
+    assert dblp.policy_three_level(delta, 0.5, 10_000, 50_000, 100_000) == \
+        oracle.policy_three_level(delta, 0.5, 10_000, 50_000, 100_000)
+    assert dblp.policy_linear(delta, 0.5, 20_000, 150_000) == oracle.policy_linear(delta, 0.5, 20_000, 150_000)
+
+
+def test_null_context_calls_return_einval_without_a_gpu():
+    L = dblp.lib()
+    assert L.dblp_begin_round(None, 1) == binding.EINVAL
+    assert L.dblp_destroy(None) == binding.OK
+    assert L.dblp_layout(None, None, None, None) == binding.EINVAL

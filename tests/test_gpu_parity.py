@@ -1,0 +1,336 @@
+"""GPU parity: the HIP library (through the C-ABI) against the CPU oracle on the same seeded
+inputs.  Integer outputs (bitmaps, per-bucket counts, retransmit lists, counters) must be
+bit-exact; the fp32 aggregate must be within 1e-5 of the fp64 oracle."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from harness import (FLOAT_TOL, GpuRx, OracleRx, build_scenario, compare_results, definition_mean,
+                     run_iteration)
+
+pytestmark = pytest.mark.gpu
+
+
+def mk(W, sizes, P, loss=0.0, seed=7, place="shuffle", order="shuffle", name="t"):
+    off, cnt = wl.buckets_from_sizes(sizes)
+    return wl.Workload(name, wl.Layout(W, int(sum(sizes)), P, off, cnt), 1e-3,
+                       dict(kind="bernoulli", p=loss) if loss else dict(kind="none"),
+                       place, order, dict(kind="fixed", ppm=0), seed=seed)
+
+
+def both(sc):
+    o, g = OracleRx(sc), GpuRx(sc)
+    o.packetize_all()
+    g.packetize_all()
+    return o, g
+
+
+def run_both(sc, ppm):
+    o, g = both(sc)
+    ref = run_iteration(o, sc, ppm)
+    got = run_iteration(g, sc, ppm)
+    return compare_results(got, ref, sc), got, ref
+
+
+# ------------------------------------------------------------------------------ inputs
+def test_device_generator_matches_cpu_generator():
+    import torch
+    for (w, it, e0, n, tail) in [(0, 0, 0, 1 << 20, 0), (5, 3, 2**33 + 11, 100_003, 10000)]:
+        d = torch.empty(n, dtype=torch.float32, device="cuda")
+        wl.grad_fill_device(d.data_ptr(), wl.MASTER_SEED, w, it, e0, n, 1e-4, tail, 100.0,
+                            torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        ref = wl.grad_values(wl.MASTER_SEED, w, it, e0, n, 1e-4, tail, 100.0)
+        assert np.array_equal(d.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
+@pytest.mark.parametrize("W,sizes,P,place", [(2, [1000, 37, 5], 16, "worker_major"), (3, [366 * 70 + 9, 1, 400], 366, "shuffle"),
+                                             (4, [5000], 256, "interleave"), (2, [4096 + 17], 1024, "shuffle"), (1, [9], 1, "shuffle")])
+def test_packetize_bytes_match_oracle(W, sizes, P, place):
+    sc = build_scenario(mk(W, sizes, P, place=place))
+    o, g = both(sc)
+    assert np.array_equal(g.packets.cpu().numpy(), o.packets)
+    assert np.array_equal(g.src.cpu().numpy().view(np.uint16), o.src)
+
+
+# ------------------------------------------------------------------------------ small / ragged
+CASES = [
+    # W, bucket sizes, P, loss, bound ppm
+    (1, [5], 2, 0.0, 0),
+    (2, [3], 2, 0.3, 0),
+    (3, [7, 1, 12, 4], 3, 0.3, 100_000),
+    (4, [1000, 37, 2048], 16, 0.1, 50_000),
+    (5, [70_001, 13, 29_999], 100, 0.05, 20_000),
+    (8, [366 * 300 + 5, 1, 366, 365, 367, 50_000], 366, 0.02, 50_000),      # several tiles, ragged tails
+    (16, [1024 * 65 + 3, 1023, 1025], 1024, 0.03, 30_000),
+    (32, [200_000, 77], 366, 0.05, 10_000),
+    (64, [30_000], 50, 0.2, 150_000),
+    (7, [256 * 130], 256, 0.01, 0),
+    (3, [4_000_000], 1000, 0.01, 8_000),                                     # one bucket = whole-round accounting
+    (2, [65535 * 3 + 1], 65535, 0.0, 0),                                     # maximum packet length
+]
+
+
+@pytest.mark.parametrize("W,sizes,P,loss,ppm", CASES)
+def test_parity_small_and_ragged(W, sizes, P, loss, ppm):
+    stats, got, ref = run_both(build_scenario(mk(W, sizes, P, loss)), ppm)
+    assert stats["rel_to_addends"] <= FLOAT_TOL
+
+
+@pytest.mark.parametrize("place,order", [("worker_major", "identity"), ("worker_major", "reverse"),
+                                         ("interleave", "identity"), ("shuffle", "shuffle")])
+def test_result_is_bitwise_independent_of_arrival_permutation(place, order):
+    base = mk(8, [366 * 200 + 7, 5000], 366, 0.05, place="worker_major", order="identity")
+    sc0 = build_scenario(base)
+    g0 = GpuRx(sc0); g0.packetize_all()
+    r0 = run_iteration(g0, sc0, 20_000)
+    sc1 = build_scenario(base, place=place, order=order)
+    g1 = GpuRx(sc1); g1.packetize_all()
+    r1 = run_iteration(g1, sc1, 20_000)
+    assert np.array_equal(r0["out"].view(np.uint32), r1["out"].view(np.uint32))
+    assert np.array_equal(r0["bitmap"], r1["bitmap"]) and r0["norm"] == r1["norm"]
+    assert all(np.array_equal(a["list"], b["list"]) for a, b in zip(r0["probes"], r1["probes"]))
+
+
+def test_zero_loss_equals_fp32_sequential_mean_exactly():
+    """No loss: the GPU sums workers in index order in fp32 and scales by 1/W (W a power of two)."""
+    sc = build_scenario(mk(4, [100_000, 333], 366))
+    g = GpuRx(sc); g.packetize_all()
+    res = run_iteration(g, sc, 0)
+    s = sc.grad(0).copy()
+    for w in range(1, 4):
+        s = (s + sc.grad(w)).astype(np.float32)
+    assert np.array_equal(res["out"], s * np.float32(0.25))
+    assert res["rounds"] == 0 and res["probes"][0]["met"]
+
+
+def test_multiple_batches_accumulate_into_existing_spans():
+    """Arrivals delivered in three separate batches, workers interleaved: later batches add to
+    spans that earlier batches wrote (read-modify-write path) and never double count."""
+    sc = build_scenario(mk(6, [366 * 90 + 11, 2000], 366, 0.1, place="worker_major", order="identity"))
+    L = sc.L
+    n = L.W * L.n_pkts
+    rng = np.random.default_rng(3)
+    part = rng.integers(0, 3, size=n)
+    o, g = both(sc)
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        for k in range(3):
+            order = np.flatnonzero(part == k).astype(np.uint32)
+            rx.apply(0, n, sc.batches[0].mask, order)
+        rx.apply(0, n, sc.batches[0].mask, None)   # everything again: all duplicates
+    assert np.array_equal(g.bitmap(), o.bitmap()) and np.array_equal(o.bitmap(), sc.survive0)
+    assert g.counters() == o.counters()
+    assert o.counters()["duplicate"] == int(sc.survive0.sum())
+    ref, got = o.finalize(), g.finalize().astype(np.float64)
+    assert np.allclose(ref, definition_mean(sc, sc.survive0), rtol=1e-14, atol=0)
+    from harness import abs_scale
+    scale = abs_scale(sc, sc.survive0)
+    nz = scale > 0
+    assert (np.abs(got - ref)[nz] / scale[nz]).max() <= FLOAT_TOL and np.all(got[~nz] == 0)
+
+
+def test_stale_duplicate_and_invalid_packets():
+    sc = build_scenario(mk(2, [100, 7], 10, place="worker_major", order="identity"))
+    o, g = both(sc)
+    p = o.packets.reshape(-1, sc.L.stride)
+    p[0, 0:4] = np.frombuffer(np.uint32(11).tobytes(), np.uint8)        # seq out of range
+    p[1, 6:8] = np.frombuffer(np.uint16(9).tobytes(), np.uint8)         # wrong length
+    p[10, 6:8] = np.frombuffer(np.uint16(10).tobytes(), np.uint8)       # tail packet claiming full length
+    p[3, 4:6] = np.frombuffer(np.uint16(sc.rnd_id - 1).tobytes(), np.uint8)   # previous round
+    o.src[2] = 2                                                        # worker out of range
+    g.upload_packets(o.packets, o.src)
+    order = np.concatenate([np.arange(22), [22, 1000], [5, 5, 6]]).astype(np.uint32)
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        rx.apply(0, 22, None, order)
+    assert o.counters() == dict(accepted=17, duplicate=3, stale=1, invalid=6)
+    assert g.counters() == o.counters()
+    assert np.array_equal(g.bitmap(), o.bitmap())
+    assert np.allclose(g.finalize(), o.finalize(), rtol=1e-6, atol=0)
+
+
+def test_first_arrival_of_conflicting_copies_wins():
+    """Two slots claim the same (worker, seq) with different payloads: the earlier arrival is used."""
+    sc = build_scenario(mk(1, [40], 10, place="worker_major", order="identity"))
+    o, g = both(sc)
+    p = o.packets.reshape(-1, sc.L.stride)
+    p[3, :8] = p[2, :8]                     # slot 3 now also claims seq 2 (with seq 3's payload)
+    g.upload_packets(o.packets, o.src)
+    for order in ([0, 1, 2, 3], [0, 1, 3, 2], [3, 2, 1, 0]):
+        for rx in (o, g):
+            rx.begin_round(sc.rnd_id)
+            rx.apply(0, 4, None, np.array(order, dtype=np.uint32))
+        assert g.counters() == o.counters() == dict(accepted=3, duplicate=1, stale=0, invalid=0)
+        assert np.array_equal(g.finalize().astype(np.float64), o.finalize())
+
+
+def test_whole_round_stale_leaves_everything_zero():
+    sc = build_scenario(mk(3, [5000], 64))
+    o, g = OracleRx(sc), GpuRx(sc)
+    o.packetize_all(rnd_id=sc.rnd_id + 1)
+    g.packetize_all(rnd_id=sc.rnd_id + 1)
+    ref = run_iteration_noloop(o, sc)
+    got = run_iteration_noloop(g, sc)
+    assert got["counters"] == ref["counters"] and ref["counters"]["stale"] == 3 * sc.L.n_pkts
+    assert not got["out"].any() and not got["bitmap"].any() and got["norm"] == 0.0
+
+
+def run_iteration_noloop(rx, sc):
+    rx.begin_round(sc.rnd_id)
+    for b in sc.batches:
+        rx.apply(b.slot_base, b.n_slots, b.mask, b.order)
+    out = rx.finalize()
+    norm, delta, crit = rx.phase_signal()
+    return dict(out=out, norm=norm, bitmap=rx.bitmap(), counters=rx.counters())
+
+
+# ------------------------------------------------------------------------------ probe edge cases
+def test_bound_extremes_and_list_capacity():
+    sc = build_scenario(mk(4, [64 * 50] * 5, 50, 0.2))
+    o, g = both(sc)
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        b = sc.batches[0]
+        rx.apply(0, b.n_slots, b.mask, b.order)
+    for ppm in (0, 1_000_000, 200_000, 250_000):
+        mo, lo, co, meto = o.loss_account(ppm)
+        mg, lg, cg, metg = g.loss_account(ppm)
+        assert np.array_equal(mo, mg) and np.array_equal(lo, lg) and (co, meto) == (cg, metg)
+    mo, lo, co, _ = o.loss_account(0)
+    assert co == int((1 - sc.survive0).sum())
+    mg, lg, cg, metg = g.loss_account(0, capacity=10)       # truncated list
+    assert cg == co and not metg and np.array_equal(lg, lo[:10])
+    count, met, trunc = g.agg.loss_account(0, None, None, 0)
+    assert trunc and count == co
+
+
+def test_empty_batch_and_nothing_received():
+    sc = build_scenario(mk(2, [1000], 10))
+    o, g = both(sc)
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        rx.apply(0, 200, None, np.zeros(0, dtype=np.uint32), 0)
+    assert g.counters() == o.counters() == dict(accepted=0, duplicate=0, stale=0, invalid=0)
+    mo, lo, co, meto = o.loss_account(0)
+    mg, lg, cg, metg = g.loss_account(0)
+    assert np.array_equal(mo, mg) and np.array_equal(lo, lg) and co == cg == 200
+    assert not g.finalize().any()
+    assert g.phase_signal()[0] == 0.0
+
+
+def test_api_errors():
+    import torch
+    from paper_2605_01989_amd import DblpError, binding
+    import paper_2605_01989_amd as dblp
+    sc = build_scenario(mk(2, [1000], 10))
+    g = GpuRx(sc)
+    with pytest.raises(DblpError) as e:
+        g.apply(0, 200, None, None)                       # before begin_round
+    assert e.value.code == binding.ESTATE
+    g.begin_round(1)
+    with pytest.raises(DblpError) as e:
+        g.agg.phase_signal()                              # no finalize yet
+    assert e.value.code == binding.ESTATE
+    with pytest.raises(DblpError) as e:
+        g.agg.finalize(g.d_out, compensation=1)
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(DblpError) as e:
+        g.agg.apply_arrivals(g.packets[8:], g.src, 10)    # misaligned packet buffer
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(DblpError) as e:
+        g.agg.loss_account(1_000_001, g.d_missing, g.d_list)
+    assert e.value.code == binding.EINVAL
+    grad = torch.zeros(500, device="cuda")
+    with pytest.raises(DblpError) as e:                   # packets reach beyond the gradient window
+        g.agg.packetize(0, 1, grad, 0, 0, 100, g.packets, g.src)
+    assert e.value.code == binding.EINVAL
+    bad_map = torch.full((50,), 10_000, dtype=torch.int32, device="cuda")
+    with pytest.raises(DblpError) as e:                   # slot map points outside the buffer
+        g.agg.packetize(0, 1, grad, 0, 0, 50, g.packets, g.src, d_slot_map=bad_map)
+    assert e.value.code == binding.EINVAL
+    for bad in (dict(n_workers=0), dict(n_workers=65), dict(payload_floats=0), dict(bucket_cnt=[999])):
+        kw = dict(n_workers=2, n_elems=1000, payload_floats=10, bucket_off=[0], bucket_cnt=[1000])
+        kw.update(bad)
+        with pytest.raises(DblpError):
+            dblp.Aggregator(**kw)
+
+
+# ------------------------------------------------------------------------------ phase signal
+def test_phase_signal_on_a_vector_and_truth_table():
+    import torch
+    sc = build_scenario(mk(2, [100_003], 100))
+    g = GpuRx(sc)
+    g.begin_round(1)
+    v = torch.from_numpy(sc.grad(0)).cuda()
+    ref = float(np.sqrt((sc.grad(0).astype(np.float64) ** 2).sum()))
+    norm, delta, crit = g.agg.phase_signal(v)
+    assert abs(norm - ref) <= 1e-6 * ref and crit and np.isinf(delta)
+    for prev_mul, want in [(2.0, True), (1.0 / 1.5, True), (1.0 / 0.51, False), (1.0, False)]:
+        g.agg.set_prev_norm(norm * prev_mul)
+        n2, d2, c2 = g.agg.phase_signal(v)
+        assert n2 == norm and c2 == want and abs(d2 - abs(prev_mul - 1) / prev_mul) < 1e-9
+    assert g.agg.get_prev_norm() == norm
+
+
+# ------------------------------------------------------------------------------ named workloads
+def test_cfg1_full():
+    stats, got, ref = run_both(build_scenario(wl.workload("cfg1")), 50_000)
+    assert ref["counters"]["accepted"] >= int(0.985 * 16384)
+    print("cfg1", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+
+
+def test_cfg2_full():
+    stats, got, ref = run_both(build_scenario(wl.workload("cfg2")), 50_000)
+    print("cfg2", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+
+
+def test_cfg3_schedule_scaled_down():
+    """GPT-2-small tensor table scaled to 6M elements, Gilbert-Elliott loss, 12 iterations of the
+    three-level policy driven by the phase signal.  The bound fed to both sides comes from the
+    oracle's signal; the GPU's signal must map to the same bound."""
+    import oracle as orc
+    import paper_2605_01989_amd as dblp
+    w = wl.scaled_down(wl.workload("cfg3"), 6_000_000)
+    w = dataclasses.replace(w, scale_schedule=tuple(w.scale_schedule[8:20]), iterations=12)
+    pol = w.policy
+    bound = pol["ppm"][0]                         # first iteration: tight
+    prev_o = prev_g = None
+    seen = set()
+    for it in range(w.iterations):
+        sc = build_scenario(w, it)
+        o, g = both(sc)
+        o.o.set_prev_norm(prev_o)
+        g.agg.set_prev_norm(prev_g)
+        ref = run_iteration(o, sc, bound)
+        got = run_iteration(g, sc, bound)
+        compare_results(got, ref, sc)
+        prev_o, prev_g = ref["norm"], got["norm"]
+        nb_o = orc.policy_three_level(ref["rel_delta"], pol["eta"], *pol["ppm"])
+        nb_g = dblp.policy_three_level(got["rel_delta"], pol["eta"], *pol["ppm"])
+        assert nb_o == nb_g
+        seen.add(bound)
+        bound = nb_o
+    assert seen == set(pol["ppm"]), seen          # the schedule visits all three levels
+
+
+def test_cfg4_microburst_scaled_down():
+    w = wl.scaled_down(wl.workload("cfg4"), 20_000_000)
+    stats, got, ref = run_both(build_scenario(w), 80_000)
+    assert ref["rounds"] >= 1
+    print("cfg4s", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+
+
+def test_cfg5_chunked_scaled_down():
+    """Chunk-streamed application (44 buckets per step), W=32, heavy-tailed values, burst loss."""
+    w = wl.workload("cfg5")
+    L = w.layout
+    off, cnt = wl.buckets_fixed(4_000_000, L.P, 64)
+    w = dataclasses.replace(w, layout=wl.Layout(L.W, 4_000_000, L.P, off, cnt))
+    sc = build_scenario(w)
+    assert len(sc.batches) == 4
+    stats, got, ref = run_both(sc, 20_000)
+    assert ref["rounds"] >= 1
+    print("cfg5s", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
