@@ -1,0 +1,312 @@
+#!/usr/bin/env python3
+"""Benchmark of the DBLP receiver hot path on one MI355X.
+
+A step is one full iteration of the receiver over one round of synthetic input that is
+already resident in HBM: begin_round -> apply_arrivals (one call per chunk step) ->
+loss_account -> simulated retransmissions until every (worker, bucket) meets the bound ->
+finalize -> phase_signal -> next bound.  Packetisation, gradient generation and loss-mask
+generation happen before the timed region.
+
+Prints ONE JSON line (see --help for the knobs).  `value` is aggregated gradient GB/s:
+accepted payload bytes / wall time of the timed steps.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; later rounds lose nothing
+
+# HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# keyed by the SHA-256 of the kernel source it was measured on; anything else reports null.
+# value = measured bytes / algorithmic bytes per launch on the default workload.
+PMC_TRAFFIC_RATIO: dict[str, float] = {}
+
+
+def _kernel_source_hash() -> str:
+    src = os.path.join(ROOT, "paper_2605_01989_amd", "csrc", "dblp_agg.hip")
+    return hashlib.sha256(open(src, "rb").read()).hexdigest()
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class DeviceJob:
+    """One workload with every input resident in HBM, driven through the C-ABI binding."""
+
+    def __init__(self, w, n_masks: int, place: str | None = None, order: str | None = None,
+                 drawn_rounds: int = BENCH_DRAWN_ROUNDS):
+        import torch
+        import paper_2605_01989_amd as dblp
+        import workloads as wl
+        self.torch, self.wl, self.w = torch, wl, w
+        L = self.L = w.layout
+        self.place, self.order = place or w.place, order or w.order
+        self.rnd_id = 1
+        self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5))
+        self.n_slots = L.W * L.n_pkts
+        dev = "cuda"
+        t0 = time.time()
+        self.packets = torch.empty(self.n_slots * L.stride, dtype=torch.uint8, device=dev)
+        self.src = torch.empty(self.n_slots, dtype=torch.int16, device=dev)
+        self.d_out = torch.empty(L.N, dtype=torch.float32, device=dev)
+        self.d_missing = torch.empty(L.W * L.B, dtype=torch.int32, device=dev)
+        self.list_cap = max(self.n_slots // 8, 1 << 16)
+        self.d_list = torch.empty(self.list_cap, dtype=torch.int64, device=dev)
+        # placement and arrival orders (host generated, seeded)
+        self.slot_of = wl.placement_chunked(self.place, L, w.chunk_buckets, w.seed, 0)
+        self.d_slot_of = torch.from_numpy(self.slot_of.reshape(-1).view(np.int32)).to(dev)
+        self.chunks = []
+        for c, (s0, s1) in enumerate(wl.chunk_seq_ranges(L, w.chunk_buckets)):
+            n = L.W * (s1 - s0)
+            o = wl.arrival_order(self.order, n, w.seed, c)
+            d_o = None if o is None else torch.from_numpy(o.view(np.int32)).to(dev)
+            self.chunks.append(dict(s0=s0, s1=s1, base=L.W * s0, n=n, d_order=d_o))
+        log(f"[bench] placement/order ready {time.time() - t0:.1f}s")
+        self._generate_packets()
+        log(f"[bench] packets resident {time.time() - t0:.1f}s ({self.packets.numel() / 1e9:.1f} GB)")
+        # first-transmission masks per step, retransmission survival per drawn round
+        self.masks = [self._mask_for(it) for it in range(n_masks)]
+        self.d_survive = {}
+        for r in range(1, drawn_rounds + 1):
+            s = w.survive(0, r, self.slot_of)
+            self.d_survive[r] = torch.from_numpy(s.reshape(-1)).to(dev)
+        torch.cuda.synchronize()
+        log(f"[bench] masks ready {time.time() - t0:.1f}s")
+
+    # -- input preparation (outside the timed region) ------------------------------------
+    def _generate_packets(self):
+        torch, wl, w, L = self.torch, self.wl, self.w, self.L
+        stream = torch.cuda.current_stream().cuda_stream
+        max_elems = 0
+        for ch in self.chunks:
+            b0 = int(np.searchsorted(L.first_seq, ch["s0"], side="right") - 1)
+            b1 = int(np.searchsorted(L.first_seq, ch["s1"] - 1, side="right") - 1)
+            ch["e0"] = int(L.bucket_off[b0])
+            ch["e1"] = int(L.bucket_off[b1] + L.bucket_cnt[b1])
+            max_elems = max(max_elems, ch["e1"] - ch["e0"])
+        grad = torch.empty(max_elems, dtype=torch.float32, device="cuda")
+        for ch in self.chunks:
+            ne = ch["e1"] - ch["e0"]
+            for wk in range(L.W):
+                wl.grad_fill_device(grad.data_ptr(), w.seed, wk, 0, ch["e0"], ne, w.sigma_at(0),
+                                    w.tail_ppm, w.tail_mul, stream)
+                d_map = self.d_slot_of[wk * L.n_pkts + ch["s0"]: wk * L.n_pkts + ch["s1"]]
+                self.agg.packetize(wk, self.rnd_id, grad[:ne], ch["e0"], ch["s0"], ch["s1"] - ch["s0"],
+                                   self.packets, self.src, d_slot_map=d_map, n_slots=self.n_slots)
+        del grad
+
+    def _pack_bits(self, bits):
+        torch = self.torch
+        n = bits.numel()
+        pad = (-n) % 64
+        if pad:
+            bits = torch.cat([bits, torch.zeros(pad, dtype=torch.uint8, device=bits.device)])
+        weights = torch.tensor([1, 2, 4, 8, 16, 32, 64, 128], dtype=torch.uint8, device=bits.device)
+        return (bits.view(-1, 8) * weights).sum(dim=1, dtype=torch.uint8).view(torch.int64)
+
+    def _mask_for(self, it: int):
+        """Per chunk step: 64-bit words, bit s = local slot s survived the first transmission."""
+        torch = self.torch
+        surv = self.w.survive(it, 0, self.slot_of)
+        d_s = torch.from_numpy(surv.reshape(-1)).cuda()
+        by_slot = torch.zeros(self.n_slots, dtype=torch.uint8, device="cuda")
+        by_slot[self.d_slot_of.long()] = d_s
+        out = [self._pack_bits(by_slot[ch["base"]: ch["base"] + ch["n"]]) for ch in self.chunks]
+        return dict(words=out, lost=int(surv.size - int(surv.sum())))
+
+    # -- the timed path --------------------------------------------------------------------
+    def step(self, it: int, bound_ppm: int, scale_ratio: float = 1.0) -> dict:
+        """One iteration.  scale_ratio = s_{t-1}/s_t of the workload's gradient-scale schedule:
+        the resident gradient is not rescaled between steps, so the previous norm is rescaled
+        instead, which gives Eq. 1 the same relative change."""
+        torch, agg, L = self.torch, self.agg, self.L
+        st = L.stride
+        m = self.masks[it % len(self.masks)]
+        agg.begin_round(self.rnd_id)
+        for ch, words in zip(self.chunks, m["words"]):
+            agg.apply_arrivals(self.packets[ch["base"] * st:], self.src[ch["base"]:], ch["n"], words,
+                               ch["d_order"], ch["n"])
+        rounds, resent = 0, 0
+        while True:
+            count, met, trunc = agg.loss_account(bound_ppm, self.d_missing, self.d_list)
+            if trunc:
+                raise RuntimeError(f"retransmit list ({count}) exceeds its buffer ({self.list_cap})")
+            if met:
+                break
+            rounds += 1
+            # the simulated sender + network: resend the listed packets, redraw their loss
+            lst = self.d_list[:count]
+            idx = (lst >> 32) * L.n_pkts + (lst & 0xFFFFFFFF)
+            if rounds in self.d_survive:
+                idx = idx[self.d_survive[rounds][idx].bool()]
+            slots = self.d_slot_of[idx]
+            resent += int(slots.numel())
+            agg.apply_arrivals(self.packets, self.src, self.n_slots, None, slots, slots.numel())
+        agg.finalize(self.d_out)
+        prev = agg.get_prev_norm()
+        if prev is not None:
+            agg.set_prev_norm(prev * scale_ratio)
+        norm, delta, crit = agg.phase_signal()
+        return dict(rounds=rounds, resent=resent, norm=norm, rel_delta=delta, critical=crit,
+                    lost_first=m["lost"], list_first=None)
+
+
+def next_bound(w, rel_delta: float, critical: bool) -> int:
+    import paper_2605_01989_amd as dblp
+    p = w.policy
+    if p["kind"] == "fixed":
+        return p["ppm"]
+    if p["kind"] == "two_level":
+        return dblp.policy_two_level(critical, p["low_ppm"], p["high_ppm"])
+    if p["kind"] == "three_level":
+        return dblp.policy_three_level(rel_delta, p["eta"], *p["ppm"])
+    if p["kind"] == "linear":
+        return dblp.policy_linear(rel_delta, p["eta"], p["lo_ppm"], p["hi_ppm"])
+    raise ValueError(p["kind"])
+
+
+def first_bound(w) -> int:
+    p = w.policy
+    return {"fixed": lambda: p["ppm"], "two_level": lambda: p["low_ppm"],
+            "three_level": lambda: p["ppm"][0], "linear": lambda: p["lo_ppm"]}[p["kind"]]()
+
+
+def cpu_baseline(w, target_elems: int) -> dict:
+    """The oracle, as it stands, timed on this host on a bounded sample of the same workload:
+    same W, P, bucket shape, loss process, placement and order, smaller gradient."""
+    import workloads as wl
+    from harness import OracleRx, build_scenario, run_iteration
+    ws = w if w.layout.N <= target_elems else wl.scaled_down(w, target_elems)
+    sc = build_scenario(ws, 0)
+    rx = OracleRx(sc)
+    rx.packetize_all()
+    t0 = time.perf_counter()
+    res = run_iteration(rx, sc, first_bound(ws))
+    dt = time.perf_counter() - t0
+    L = ws.layout
+    fill = L.N / (L.n_pkts * L.P)
+    payload = res["counters"]["accepted"] * 4 * L.P * fill
+    return dict(value=payload / dt / 1e9, unit="GB/s", cores=1, kind="oracle",
+                sample=f"{ws.name}: W={L.W} N={L.N} P={L.P} packets={L.W * L.n_pkts} one iteration "
+                       f"incl. {res['rounds']} retransmission round(s), {dt:.2f} s single-threaded",
+                packets_per_s=res["counters"]["accepted"] / dt)
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5 (default: the largest, cfg5)")
+    ap.add_argument("--place", default=None, help="override wire placement: worker_major|interleave|shuffle")
+    ap.add_argument("--order", default=None, help="override arrival order: identity|shuffle|reverse")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-elems", type=int, default=48_000_000)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (all workers are simulated in that GPU's "
+                 "memory); --gpus must be 1")
+
+    import torch
+    import workloads as wl
+    from paper_2605_01989_amd import binding
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = wl.workload(args.workload)
+    L = w.layout
+    total = args.warmup + args.steps
+    job = DeviceJob(w, n_masks=total, place=args.place, order=args.order)
+    agg = job.agg
+    sched = w.scale_schedule
+
+    def ratio(t):
+        """s_{t-1}/s_t of the gradient-scale schedule (1 at its start and when there is none)."""
+        if not sched or t % len(sched) == 0:
+            return 1.0
+        return sched[t % len(sched) - 1] / sched[t % len(sched)]
+
+    bound = first_bound(w)
+    for t in range(args.warmup):
+        r = job.step(t, bound, ratio(t))
+        log(f"[bench] warmup {t}: bound={bound} rounds={r['rounds']} resent={r['resent']} delta={r['rel_delta']:.4f}")
+        bound = next_bound(w, r["rel_delta"], r["critical"])
+    agg.profile_enable(True)
+    for k in range(binding.K_FINALIZE + 1):
+        agg.profile_read(k)
+    torch.cuda.synchronize()
+    c0 = None
+    accepted_total, resent_total, rounds_total = 0, 0, 0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall0 = time.perf_counter()
+    ev0.record()
+    per_step = []
+    for t in range(args.warmup, total):
+        r = job.step(t, bound, ratio(t))
+        c = agg.get_counters()
+        accepted_total += c["accepted"]
+        resent_total += r["resent"]
+        rounds_total += r["rounds"]
+        per_step.append(dict(bound_ppm=bound, rounds=r["rounds"], resent=r["resent"], accepted=c["accepted"]))
+        bound = next_bound(w, r["rel_delta"], r["critical"])
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_wall0
+    ms_per_step = wall * 1e3 / args.steps
+    prof = {name: agg.profile_read(k) for name, k in
+            (("index", binding.K_INDEX), ("gather", binding.K_GATHER), ("probe", binding.K_PROBE),
+             ("finalize", binding.K_FINALIZE))}
+    agg.profile_enable(False)
+
+    fill = L.N / (L.n_pkts * L.P)
+    payload_bytes = accepted_total * 4 * L.P * fill
+    value = payload_bytes / wall / 1e9
+    # dominant kernel: gather_accumulate.  Algorithmic bytes = every accepted packet read once
+    # (header + payload + padding = stride) + the accumulator written once per iteration.
+    g_ms, g_n = prof["gather"]
+    g_bytes = accepted_total * L.stride + args.steps * 4 * L.N
+    achieved = g_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
+    ratio_pmc = PMC_TRAFFIC_RATIO.get(_kernel_source_hash())
+    roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=round(achieved / HBM_PEAK_GBPS, 4), kernel="gather_accumulate",
+                    launches=g_n, avg_launch_ms=round(g_ms / max(g_n, 1), 4),
+                    algorithmic_bytes_per_launch=round(g_bytes / max(g_n, 1)),
+                    traffic=None if ratio_pmc is None else round(ratio_pmc * g_bytes / max(g_n, 1)))
+    # whole-path algorithmic bytes: + finalize (read acc, write out) per iteration
+    path_bytes = g_bytes + args.steps * 8 * L.N
+    out = dict(metric="aggregated_gradient_GBps", value=round(value, 2), unit="GB/s", n_gpus=1,
+               steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 3),
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
+               config=dict(workload=f"{w.name}: W={L.W} N={L.N} P={L.P} buckets={L.B} "
+                                    f"packets/round={L.W * L.n_pkts} loss={w.loss['kind']} "
+                                    f"policy={w.policy['kind']}",
+                           placement=job.place, arrival_order=job.order,
+                           chunk_steps=len(job.chunks), resident_packet_GB=round(job.packets.numel() / 1e9, 2)),
+               packets_per_s=round(accepted_total / wall, 1),
+               path_hbm_frac=round(path_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),
+               retransmission_rounds=rounds_total, resent_packets=resent_total,
+               gpu_event_ms_per_step=round(ev0.elapsed_time(ev1) / args.steps, 3),
+               kernel_ms_per_step={k: round(v[0] / args.steps, 4) for k, v in prof.items()},
+               per_step=per_step, roofline=roofline)
+    if not args.no_cpu_baseline:
+        del job
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

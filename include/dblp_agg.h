@@ -164,6 +164,18 @@ int dblp_get_counters(dblp_ctx* ctx, uint64_t h_counters[4]);
 int dblp_set_prev_norm(dblp_ctx* ctx, double norm, int have);
 int dblp_get_prev_norm(const dblp_ctx* ctx, double* h_norm, int* h_have);
 
+/* Optional tracing: with profiling on, the launches of the kernels below are bracketed by
+ * HIP events on the context's stream.  dblp_profile_read synchronises the stream, returns
+ * the summed duration (milliseconds) and number of launches recorded for one kernel group
+ * since the last read of that group, and forgets them. */
+#define DBLP_K_INDEX 0    /* header parse / validation / arrival index */
+#define DBLP_K_GATHER 1   /* payload gather + accumulate */
+#define DBLP_K_PROBE 2    /* loss count + prefix + retransmit list (three launches, one bracket) */
+#define DBLP_K_FINALIZE 3 /* zero-fill mean + partial sums of squares */
+#define DBLP_K_COUNT 4
+int dblp_profile_enable(dblp_ctx* ctx, int on);
+int dblp_profile_read(dblp_ctx* ctx, int kernel, double* h_total_ms, uint64_t* h_launches);
+
 /* Text of the last error on this context (valid until the next call on it). */
 const char* dblp_last_error(const dblp_ctx* ctx);
 

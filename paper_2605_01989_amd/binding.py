@@ -17,11 +17,12 @@ OK, EINVAL, ENOMEM, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4, -5
 _NAMES = {EINVAL: "DBLP_EINVAL", ENOMEM: "DBLP_ENOMEM", ECAPACITY: "DBLP_ECAPACITY",
           ESTATE: "DBLP_ESTATE", EHIP: "DBLP_EHIP"}
 COMP_ZEROFILL_MEAN = 0
+K_INDEX, K_GATHER, K_PROBE, K_FINALIZE = 0, 1, 2, 3
 
 EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_begin_round", "dblp_packetize",
            "dblp_apply_arrivals", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
            "dblp_get_bitmap", "dblp_get_counters", "dblp_set_prev_norm", "dblp_get_prev_norm",
-           "dblp_last_error", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear"]
+           "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear"]
 
 
 class DblpError(RuntimeError):
@@ -66,6 +67,8 @@ def lib():
         L.dblp_get_counters.argtypes = [vp, ctypes.POINTER(u64)]
         L.dblp_set_prev_norm.argtypes = [vp, dbl, i32]
         L.dblp_get_prev_norm.argtypes = [vp, ctypes.POINTER(dbl), ctypes.POINTER(i32)]
+        L.dblp_profile_enable.argtypes = [vp, i32]
+        L.dblp_profile_read.argtypes = [vp, i32, ctypes.POINTER(dbl), ctypes.POINTER(u64)]
         L.dblp_last_error.argtypes = [vp]
         L.dblp_last_error.restype = ctypes.c_char_p
         for name in ("dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear"):
@@ -172,6 +175,15 @@ class Aggregator:
         c = (ctypes.c_uint64 * 4)()
         self._check(lib().dblp_get_counters(self._h, c))
         return dict(accepted=int(c[0]), duplicate=int(c[1]), stale=int(c[2]), invalid=int(c[3]))
+
+    def profile_enable(self, on: bool):
+        self._check(lib().dblp_profile_enable(self._h, int(on)))
+
+    def profile_read(self, kernel: int):
+        """(total milliseconds, launches) of one kernel group since the last read."""
+        ms, n = ctypes.c_double(), ctypes.c_uint64()
+        self._check(lib().dblp_profile_read(self._h, kernel, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, int(n.value)
 
     def set_prev_norm(self, norm):
         self._check(lib().dblp_set_prev_norm(self._h, 0.0 if norm is None else norm, int(norm is not None)))

@@ -25,6 +25,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <vector>
+
 #include "../../include/dblp_agg.h"
 
 typedef unsigned long long u64;
@@ -44,7 +46,6 @@ struct Geo {
     u32 n_pkts;
     u32 stride;             // bytes
     u32 units;              // stride / 16
-    u32 run;                // consecutive seqs handled together by one wave: max(1, 64 / W)
     u64 words_pw;           // bitmap words per worker
 };
 
@@ -182,57 +183,62 @@ __global__ __launch_bounds__(256) void packetize_kernel(Geo g, u32 w, u32 round,
 // ------------------------------------------------------------------------------------------
 // receiver step 1: index the arrivals
 // ------------------------------------------------------------------------------------------
+// Grid-stride over arrivals.  Per-thread tallies are reduced per wave (DPP) and per block
+// (LDS); each block then issues at most one global atomic per counter, because atomics of many
+// waves on one address serialise in L2.
 __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __restrict__ packets,
                                                       const uint16_t* __restrict__ src_worker, u64 n_slots,
                                                       const u64* __restrict__ mask, const u32* __restrict__ order,
                                                       u64 n_arrivals, u32 cur_round, const u64* __restrict__ bitmap,
                                                       u64* __restrict__ pending, u64* __restrict__ counters) {
-    u64 k = (u64)blockIdx.x * blockDim.x + threadIdx.x;
-    enum { LOST = 0, STALE, INVALID, DUP, CAND };
-    int cls = LOST;
+    __shared__ u32 sh[4][6];
+    u32 n_stale = 0, n_inv = 0, n_dup = 0, n_cand = 0;
     u32 seq_lo = 0xFFFFFFFFu, seq_hi = 0;
-    if (k < n_arrivals) {
-        u64 slot = order ? (u64)order[k] : k;
-        if (slot >= n_slots) {
-            cls = INVALID;
-        } else if (mask && !((mask[slot >> 6] >> (slot & 63)) & 1ull)) {
-            cls = LOST;                                        // never looked at
-        } else {
-            uint2 hdr = *(const uint2*)(packets + slot * g.stride);
-            u32 seq = hdr.x, round = hdr.y & 0xFFFFu, len = hdr.y >> 16;
-            u32 w = src_worker[slot];
-            if (round != cur_round) {
-                cls = STALE;
-            } else if (w >= g.W || seq >= g.n_pkts) {
-                cls = INVALID;
-            } else {
-                u32 b = find_bucket(g.first_seq, g.B, seq);
-                u64 elem; u32 want;
-                packet_span(g, seq, b, &elem, &want);
-                if (len != want) {
-                    cls = INVALID;
-                } else if ((bitmap[(u64)w * g.words_pw + (seq >> 6)] >> (seq & 63)) & 1ull) {
-                    cls = DUP;                                 // delivered by an earlier batch
-                } else {
-                    cls = CAND;
-                    atomicMin(&pending[(u64)w * g.n_pkts + seq], (k << 32) | slot);
-                    seq_lo = seq; seq_hi = seq + 1;
-                }
-            }
-        }
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    for (u64 k = (u64)blockIdx.x * blockDim.x + threadIdx.x; k < n_arrivals; k += stride) {
+        const u64 slot = order ? (u64)order[k] : k;
+        if (slot >= n_slots) { ++n_inv; continue; }
+        if (mask && !((mask[slot >> 6] >> (slot & 63)) & 1ull)) continue;   // lost: never looked at
+        const uint2 hdr = *(const uint2*)(packets + slot * g.stride);
+        const u32 seq = hdr.x, round = hdr.y & 0xFFFFu, len = hdr.y >> 16;
+        const u32 w = src_worker[slot];
+        if (round != cur_round) { ++n_stale; continue; }
+        if (w >= g.W || seq >= g.n_pkts) { ++n_inv; continue; }
+        const u32 b = find_bucket(g.first_seq, g.B, seq);
+        u64 elem; u32 want;
+        packet_span(g, seq, b, &elem, &want);
+        if (len != want) { ++n_inv; continue; }
+        if ((bitmap[(u64)w * g.words_pw + (seq >> 6)] >> (seq & 63)) & 1ull) { ++n_dup; continue; }   // earlier batch
+        ++n_cand;
+        atomicMin(&pending[(u64)w * g.n_pkts + seq], (k << 32) | slot);
+        seq_lo = seq < seq_lo ? seq : seq_lo;
+        seq_hi = seq + 1 > seq_hi ? seq + 1 : seq_hi;
     }
-    // one atomic per wave and class
-    u64 m_stale = __ballot(cls == STALE), m_inv = __ballot(cls == INVALID);
-    u64 m_dup = __ballot(cls == DUP), m_cand = __ballot(cls == CAND);
-    u32 lo = wave_reduce<OpMin>(seq_lo), hi = wave_reduce<OpMax>(seq_hi);
+    // loops above have lane-dependent trip counts; all 64 lanes are back here
+    n_stale = wave_reduce<OpAdd>(n_stale); n_inv = wave_reduce<OpAdd>(n_inv);
+    n_dup = wave_reduce<OpAdd>(n_dup); n_cand = wave_reduce<OpAdd>(n_cand);
+    seq_lo = wave_reduce<OpMin>(seq_lo); seq_hi = wave_reduce<OpMax>(seq_hi);
+    const u32 wave = threadIdx.x / WAVE;
     if (lane_id() == 0) {
-        if (m_stale) atomicAdd(&counters[C_STALE], (u64)__popcll(m_stale));
-        if (m_inv) atomicAdd(&counters[C_INVALID], (u64)__popcll(m_inv));
-        if (m_dup) atomicAdd(&counters[C_DUP_PREV], (u64)__popcll(m_dup));
-        if (m_cand) {
-            atomicAdd(&counters[C_CANDIDATES], (u64)__popcll(m_cand));
-            atomicMin(&counters[C_LO], (u64)lo);
-            atomicMax(&counters[C_HI], (u64)hi);
+        sh[wave][0] = n_stale; sh[wave][1] = n_inv; sh[wave][2] = n_dup; sh[wave][3] = n_cand;
+        sh[wave][4] = seq_lo; sh[wave][5] = seq_hi;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 t[4] = {0, 0, 0, 0}, lo = 0xFFFFFFFFu, hi = 0;
+        for (int i = 0; i < 4; ++i) {
+            for (int j = 0; j < 4; ++j) t[j] += sh[i][j];
+            lo = sh[i][4] < lo ? sh[i][4] : lo;
+            hi = sh[i][5] > hi ? sh[i][5] : hi;
+        }
+        if (t[0]) atomicAdd(&counters[C_STALE], (u64)t[0]);
+        if (t[1]) atomicAdd(&counters[C_INVALID], (u64)t[1]);
+        if (t[2]) atomicAdd(&counters[C_DUP_PREV], (u64)t[2]);
+        if (t[3]) {
+            atomicAdd(&counters[C_CANDIDATES], (u64)t[3]);
+            // the range only widens: skip the atomic when a plain read shows it would not
+            if ((u64)lo < *(volatile u64*)&counters[C_LO]) atomicMin(&counters[C_LO], (u64)lo);
+            if ((u64)hi > *(volatile u64*)&counters[C_HI]) atomicMax(&counters[C_HI], (u64)hi);
         }
     }
 }
@@ -240,12 +246,15 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
 // ------------------------------------------------------------------------------------------
 // receiver step 2: gather payloads per output packet and accumulate
 // ------------------------------------------------------------------------------------------
-#define GROUP 8   // payload loads kept in flight per lane
+#define GROUP 8      // payload loads kept in flight per lane
+#define GA_WAVES 8   // waves per block; a block owns one tile of 64 consecutive sequence numbers
+#define NONE32 0xFFFFFFFFu
 
 // Sum the payload unit `u` (16 bytes at offset 16u of each packet) over the workers in `sub`
 // (bit w set = worker w delivered this packet in this batch), ascending worker order.
+// slot32 holds worker w's slot in lane w.
 __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, u32 stride, u32 u, bool active,
-                                           u64 sub, u32 slot32, u32 lane_base) {
+                                           u64 sub, u32 slot32) {
     float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
     while (sub) {
         float4 v[GROUP];
@@ -253,9 +262,9 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
         for (int j = 0; j < GROUP; ++j) {
             v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (sub) {
-                u32 w = (u32)__builtin_ctzll(sub);
+                const u32 w = (u32)__builtin_ctzll(sub);
                 sub &= sub - 1;
-                u32 slot = (u32)__builtin_amdgcn_readlane((int)slot32, (int)(lane_base + w));
+                const u32 slot = (u32)__builtin_amdgcn_readlane((int)slot32, (int)w);
                 if (active) v[j] = *(const float4*)(packets + (u64)slot * stride + 16ull * u);
             }
         }
@@ -265,60 +274,75 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
     return a;
 }
 
-__global__ __launch_bounds__(256) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
-                                                         u64* __restrict__ pending, u64* __restrict__ bitmap,
-                                                         float* __restrict__ acc, u64* __restrict__ counters) {
+// One block per tile of 64 sequence numbers (one bitmap word per worker), grid-stride over the
+// tiles the batch touched.
+//   phase A  the block's waves split the workers: coalesced read of the arrival index, ballot
+//            -> new bitmap bits (the block owns the words, so plain stores), slots staged in LDS,
+//            index entries reset; one wave computes the 64 packets' element spans in parallel
+//   phase B  the waves split the 64 packets: per packet, 16-byte payload loads from every
+//            worker that delivered it, summed in registers in worker order, one write of the span
+__global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
+                                                                    u64* __restrict__ pending, u64* __restrict__ bitmap,
+                                                                    float* __restrict__ acc, u64* __restrict__ counters) {
+    extern __shared__ u32 sh_slot[];           // [W][64]
+    __shared__ u64 sh_elem[WAVE];
+    __shared__ u32 sh_len[WAVE];
+    __shared__ u64 sh_new[GA_WAVES], sh_old[GA_WAVES];
     const u64 lo = counters[C_LO], hi = counters[C_HI];
     if (hi == 0) return;                                    // no candidate in this batch
     const u32 lane = lane_id();
-    const u32 wave = (blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
-    const u32 n_waves = gridDim.x * blockDim.x / WAVE;
-    const u32 run = g.run, W = g.W;
-    const u32 r_lane = lane / W, w_lane = lane - r_lane * W;
-    const bool lane_used = lane < run * W;
-    const u64 wmask = (W == 64) ? NONE64 : ((1ull << W) - 1);
-    const u32 first_run = (u32)(lo / run), end_run = (u32)((hi + run - 1) / run);
+    const u32 wave = threadIdx.x / WAVE;
+    const u32 W = g.W;
+    const u32 tile_end = (u32)((hi + 63) >> 6);
     u32 accepted = 0;
 
-    for (u32 rn = first_run + wave; rn < end_run; rn += n_waves) {
-        const u32 seq0 = rn * run;
-        const u32 seq_l = seq0 + r_lane;
-        const bool valid = lane_used && seq_l < g.n_pkts;
-        u64 p = NONE64, word = 0;
-        if (valid) {
-            p = pending[(u64)w_lane * g.n_pkts + seq_l];
-            word = bitmap[(u64)w_lane * g.words_pw + (seq_l >> 6)];
+    for (u32 tile = (u32)(lo >> 6) + blockIdx.x; tile < tile_end; tile += gridDim.x) {
+        const u32 seq_l = (tile << 6) + lane;
+        const bool valid = seq_l < g.n_pkts;
+        u64 new_or = 0, old_or = 0;
+        for (u32 w = wave; w < W; w += GA_WAVES) {
+            const u64 p = valid ? pending[(u64)w * g.n_pkts + seq_l] : NONE64;
+            const bool has = p != NONE64;
+            const u64 nb = __ballot(has);
+            const u64 old = bitmap[(u64)w * g.words_pw + tile];
+            sh_slot[w * WAVE + lane] = has ? (u32)p : NONE32;
+            if (nb) {
+                if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty for the next batch
+                if (lane == 0) bitmap[(u64)w * g.words_pw + tile] = old | nb;
+            }
+            new_or |= nb; old_or |= old;
+            accepted += (u32)__popcll(nb);
         }
-        const bool has = p != NONE64;
-        const u64 hasmask = __ballot(has);
-        if (!hasmask) continue;
-        const u64 oldmask = __ballot((word >> (seq_l & 63)) & 1ull);
-        if (has) {
-            pending[(u64)w_lane * g.n_pkts + seq_l] = NONE64;          // leave the index empty for the next batch
-            atomicOr(&bitmap[(u64)w_lane * g.words_pw + (seq_l >> 6)], 1ull << (seq_l & 63));
-        }
-        accepted += (u32)__popcll(hasmask);
-        const u32 slot32 = (u32)p;
-
-        for (u32 r = 0; r < run; ++r) {
-            const u64 sub = (hasmask >> (r * W)) & wmask;
-            if (!sub) continue;
-            const bool rmw = ((oldmask >> (r * W)) & wmask) != 0;      // span already holds earlier arrivals
-            const u32 seq = seq0 + r;
-            const u32 b = find_bucket(g.first_seq, g.B, seq);
+        if (wave == GA_WAVES - 1 && valid) {
+            const u32 b = find_bucket(g.first_seq, g.B, seq_l);
             u64 elem; u32 len;
-            packet_span(g, seq, b, &elem, &len);
-            const u32 units = (len + 2 + 3) >> 2;                        // 16-byte units holding header + payload
-            float* dst0 = acc + elem - 2;                                // float position i of the packet -> dst0[i]
+            packet_span(g, seq_l, b, &elem, &len);
+            sh_elem[lane] = elem; sh_len[lane] = len;
+        }
+        if (lane == 0) { sh_new[wave] = new_or; sh_old[wave] = old_or; }
+        __syncthreads();
+        u64 new_any = 0, old_any = 0;
+        #pragma unroll
+        for (int i = 0; i < GA_WAVES; ++i) { new_any |= sh_new[i]; old_any |= sh_old[i]; }
+
+        for (u32 t = wave; t < WAVE; t += GA_WAVES) {
+            if (!((new_any >> t) & 1ull)) continue;
+            const bool rmw = (old_any >> t) & 1ull;          // span already holds earlier arrivals
+            const u64 elem = sh_elem[t];
+            const u32 len = sh_len[t];
+            const u32 slot32 = lane < W ? sh_slot[lane * WAVE + t] : NONE32;
+            const u64 sub = __ballot(slot32 != NONE32);
+            const u32 units = (len + 2 + 3) >> 2;            // 16-byte units holding header + payload
+            float* dst0 = acc + elem - 2;                    // float position i of the packet -> dst0[i]
             for (u32 u0 = 0; u0 < units; u0 += WAVE) {
                 const u32 u = u0 + lane;
                 const bool active = u < units;
-                float4 a = sum_unit(packets, g.stride, u, active, sub, slot32, r * W);
+                const float4 a = sum_unit(packets, g.stride, u, active, sub, slot32);
                 if (active) {
-                    float q[4] = {a.x, a.y, a.z, a.w};
+                    const float q[4] = {a.x, a.y, a.z, a.w};
                     #pragma unroll
                     for (int c = 0; c < 4; ++c) {
-                        u32 i4 = 4 * u + c;
+                        const u32 i4 = 4 * u + c;
                         if (i4 >= 2 && i4 - 2 < len) {
                             float* d = dst0 + i4;
                             *d = rmw ? (*d + q[c]) : q[c];
@@ -327,6 +351,7 @@ __global__ __launch_bounds__(256) void gather_accumulate(Geo g, const uint8_t* _
                 }
             }
         }
+        __syncthreads();                                     // LDS is reused by the next tile
     }
     if (lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
 }
@@ -522,7 +547,34 @@ struct dblp_ctx {
     // protocol state
     int round_open; int finalized; uint16_t round;
     double prev_norm; int have_prev;
+    // optional per-kernel timing (HIP events on the context's stream)
+    int profiling;
+    struct Timed { hipEvent_t a, b; int kernel; };
+    std::vector<Timed>* timed;        // recorded, not yet read
+    std::vector<hipEvent_t>* ev_pool; // free events
     char err[256];
+};
+
+static hipEvent_t prof_event(dblp_ctx* c) {
+    hipEvent_t e = nullptr;
+    if (!c->ev_pool->empty()) { e = c->ev_pool->back(); c->ev_pool->pop_back(); }
+    else if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); e = nullptr; }
+    return e;
+}
+
+// Brackets one kernel launch with events when profiling is on.
+struct ProfScope {
+    dblp_ctx* c; hipEvent_t a; int kernel;
+    ProfScope(dblp_ctx* c_, int kernel_) : c(c_), a(nullptr), kernel(kernel_) {
+        if (c->profiling && (a = prof_event(c))) (void)hipEventRecord(a, c->stream);
+    }
+    ~ProfScope() {
+        if (!a) return;
+        hipEvent_t b = prof_event(c);
+        if (!b) { c->ev_pool->push_back(a); return; }
+        (void)hipEventRecord(b, c->stream);
+        c->timed->push_back({a, b, kernel});
+    }
 };
 
 static int fail(dblp_ctx* c, int code, const char* what) {
@@ -563,6 +615,8 @@ extern "C" int dblp_destroy(dblp_ctx* c) {
                    c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials};
     for (void* p : dev) if (p) (void)hipFree(p);
     if (c->h_mailbox) (void)hipHostFree(c->h_mailbox);
+    if (c->timed) { for (auto& t : *c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); } delete c->timed; }
+    if (c->ev_pool) { for (auto e : *c->ev_pool) (void)hipEventDestroy(e); delete c->ev_pool; }
     free(c->h_first_seq); free(c->h_b_off); free(c->h_b_cnt);
     free(c);
     return DBLP_OK;
@@ -590,6 +644,9 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     dblp_ctx* c = (dblp_ctx*)calloc(1, sizeof *c);
     if (!c) return DBLP_ENOMEM;
     c->N = cfg->n_elems; c->eta = cfg->eta; c->device = cfg->device; c->stream = (hipStream_t)cfg->stream;
+    c->timed = new (std::nothrow) std::vector<dblp_ctx::Timed>();
+    c->ev_pool = new (std::nothrow) std::vector<hipEvent_t>();
+    if (!c->timed || !c->ev_pool) { dblp_destroy(c); return DBLP_ENOMEM; }
     c->h_first_seq = (u32*)malloc((B + 1) * sizeof(u32));
     c->h_b_off = (u64*)malloc(B * sizeof(u64));
     c->h_b_cnt = (u64*)malloc(B * sizeof(u64));
@@ -607,7 +664,6 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     g.B = B; g.P = P; g.W = cfg->n_workers; g.n_pkts = (u32)n_pkts;
     g.stride = (8 + 4 * P + 15) / 16 * 16;
     g.units = g.stride / 16;
-    g.run = 64 / g.W ? 64 / g.W : 1;
     g.words_pw = (n_pkts + 63) / 64;
 
     hipError_t e = hipSetDevice(c->device);
@@ -732,12 +788,18 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
     HIP_TRY(c, hipSetDevice(c->device));
     const Geo& g = c->g;
     hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters, 1);
-    hipLaunchKernelGGL(index_arrivals, dim3((u32)((n_arrivals + 255) / 256)), dim3(256), 0, c->stream, g,
-                       (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
-                       (u64)n_arrivals, (u32)c->round, c->d_bitmap, c->d_pending, c->d_counters);
-    const u64 runs = ((u64)g.n_pkts + g.run - 1) / g.run;
-    hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, (runs + 3) / 4, 8)), dim3(256), 0, c->stream, g,
-                       (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc, c->d_counters);
+    {
+        ProfScope ps(c, DBLP_K_INDEX);
+        hipLaunchKernelGGL(index_arrivals, dim3(grid_for(c, (n_arrivals + 255) / 256, 8)), dim3(256), 0, c->stream, g,
+                           (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
+                           (u64)n_arrivals, (u32)c->round, c->d_bitmap, c->d_pending, c->d_counters);
+    }
+    {
+        ProfScope ps(c, DBLP_K_GATHER);
+        hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, g.words_pw, 4)), dim3(GA_WAVES * WAVE),
+                           g.W * WAVE * sizeof(u32), c->stream, g, (const uint8_t*)d_packets, c->d_pending,
+                           c->d_bitmap, c->d_acc, c->d_counters);
+    }
     LAUNCH_CHECK(c, "apply_arrivals");
     c->finalized = 0;
     return DBLP_OK;
@@ -753,12 +815,15 @@ extern "C" int dblp_loss_account(dblp_ctx* c, uint32_t bound_ppm, uint32_t* d_mi
     HIP_TRY(c, hipSetDevice(c->device));
     const Geo& g = c->g;
     const u32 pairs = g.W * g.B;
-    hipLaunchKernelGGL(loss_count, dim3(grid_for(c, (pairs + 3) / 4, 8)), dim3(256), 0, c->stream, g, c->d_bitmap,
-                       bound_ppm, d_missing ? d_missing : c->d_missing, c->d_need);
-    hipLaunchKernelGGL(scan_need, dim3(1), dim3(1024), 0, c->stream, c->d_need, pairs, c->d_offs, c->d_mailbox);
-    if (retx_capacity)
-        hipLaunchKernelGGL(emit_retx, dim3(grid_for(c, (pairs + 3) / 4, 8)), dim3(256), 0, c->stream, g, c->d_bitmap,
-                           c->d_need, c->d_offs, (u64*)d_retx_list, (u64)retx_capacity);
+    {
+        ProfScope ps(c, DBLP_K_PROBE);
+        hipLaunchKernelGGL(loss_count, dim3(grid_for(c, (pairs + 3) / 4, 8)), dim3(256), 0, c->stream, g, c->d_bitmap,
+                           bound_ppm, d_missing ? d_missing : c->d_missing, c->d_need);
+        hipLaunchKernelGGL(scan_need, dim3(1), dim3(1024), 0, c->stream, c->d_need, pairs, c->d_offs, c->d_mailbox);
+        if (retx_capacity)
+            hipLaunchKernelGGL(emit_retx, dim3(grid_for(c, (pairs + 3) / 4, 8)), dim3(256), 0, c->stream, g, c->d_bitmap,
+                               c->d_need, c->d_offs, (u64*)d_retx_list, (u64)retx_capacity);
+    }
     LAUNCH_CHECK(c, "loss_account");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     const u64 total = c->h_mailbox[0];
@@ -779,8 +844,11 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
     const int pow2 = (W & (W - 1)) == 0;
     const u64 tiles = ((u64)g.n_pkts + FIN_TILE - 1) / FIN_TILE;
     const u32 grid = grid_for(c, (tiles + 3) / 4, FIN_BLOCKS_PER_CU);
-    hipLaunchKernelGGL(finalize_mean, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc, d_out,
-                       1.0f / (float)W, !pow2, (float)W, c->d_partials);
+    {
+        ProfScope ps(c, DBLP_K_FINALIZE);
+        hipLaunchKernelGGL(finalize_mean, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc, d_out,
+                           1.0f / (float)W, !pow2, (float)W, c->d_partials);
+    }
     LAUNCH_CHECK(c, "finalize");
     c->n_partials = grid;
     c->finalized = 1;
@@ -838,6 +906,29 @@ extern "C" int dblp_get_counters(dblp_ctx* c, uint64_t h[4]) {
     h[1] = tmp[C_DUP_PREV] + (tmp[C_CANDIDATES] - tmp[C_ACCEPTED]);   // earlier batches + second copies in a batch
     h[2] = tmp[C_STALE];
     h[3] = tmp[C_INVALID];
+    return DBLP_OK;
+}
+
+extern "C" int dblp_profile_enable(dblp_ctx* c, int on) {
+    if (!c) return DBLP_EINVAL;
+    c->profiling = on != 0;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_profile_read(dblp_ctx* c, int kernel, double* h_total_ms, uint64_t* h_launches) {
+    if (!c || !h_total_ms || !h_launches || kernel < 0 || kernel >= DBLP_K_COUNT) return DBLP_EINVAL;
+    HIP_TRY(c, hipSetDevice(c->device));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    double total = 0.0; u64 n = 0;
+    std::vector<dblp_ctx::Timed> keep;
+    for (auto& t : *c->timed) {
+        if (t.kernel != kernel) { keep.push_back(t); continue; }
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) { total += ms; ++n; } else (void)hipGetLastError();
+        c->ev_pool->push_back(t.a); c->ev_pool->push_back(t.b);
+    }
+    c->timed->swap(keep);
+    *h_total_ms = total; *h_launches = n;
     return DBLP_OK;
 }
 

@@ -288,13 +288,13 @@ def test_cfg2_full():
 
 
 def test_cfg3_schedule_scaled_down():
-    """GPT-2-small tensor table scaled to 6M elements, Gilbert-Elliott loss, 12 iterations of the
+    """GPT-2-small tensor table scaled to 6M elements, Gilbert-Elliott loss, 15 iterations of the
     three-level policy driven by the phase signal.  The bound fed to both sides comes from the
     oracle's signal; the GPU's signal must map to the same bound."""
     import oracle as orc
     import paper_2605_01989_amd as dblp
     w = wl.scaled_down(wl.workload("cfg3"), 6_000_000)
-    w = dataclasses.replace(w, scale_schedule=tuple(w.scale_schedule[8:20]), iterations=12)
+    w = dataclasses.replace(w, scale_schedule=tuple(w.scale_schedule[8:23]), iterations=15)
     pol = w.policy
     bound = pol["ppm"][0]                         # first iteration: tight
     prev_o = prev_g = None

@@ -237,10 +237,18 @@ def survive_bernoulli(seed, it, rnd, W, n_pkts, p) -> np.ndarray:
 def survive_gilbert_elliott(seed, it, rnd, W, n_pkts, p_good, p_bad, p_g2b, p_b2g) -> np.ndarray:
     """Per-worker two-state chain over that worker's send sequence (seq order)."""
     out = np.empty((W, n_pkts), dtype=np.uint8)
-    for w in range(W):
-        _cpu_lib().dblp_gen_gilbert_elliott(out[w].ctypes.data, n_pkts,
-                                            key(seed, STREAM_LOSS, it, rnd, w),
-                                            q32(p_good), q32(p_bad), q32(p_g2b), q32(p_b2g))
+    lib = _cpu_lib()
+
+    def one(w):   # the chain is sequential per worker; workers are independent (ctypes drops the GIL)
+        lib.dblp_gen_gilbert_elliott(out[w].ctypes.data, n_pkts, key(seed, STREAM_LOSS, it, rnd, w),
+                                     q32(p_good), q32(p_bad), q32(p_g2b), q32(p_b2g))
+    if W * n_pkts < 1 << 22:
+        for w in range(W):
+            one(w)
+    else:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            list(ex.map(one, range(W)))
     return out
 
 
