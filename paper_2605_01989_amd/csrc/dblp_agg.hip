@@ -246,8 +246,16 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
 // ------------------------------------------------------------------------------------------
 // receiver step 2: gather payloads per output packet and accumulate
 // ------------------------------------------------------------------------------------------
-#define GROUP 8      // payload loads kept in flight per lane
-#define GA_WAVES 8   // waves per block; a block owns one tile of 64 consecutive sequence numbers
+#ifndef GROUP
+#define GROUP 8             // payload loads kept in flight per lane
+#endif
+#ifndef GA_WAVES
+#define GA_WAVES 8          // waves per block
+#endif
+#ifndef GA_BLOCKS_PER_CU
+#define GA_BLOCKS_PER_CU 4
+#endif
+#define SUB 16              // consecutive sequence numbers a block handles at a time (divides 64)
 #define NONE32 0xFFFFFFFFu
 
 // Sum the payload unit `u` (16 bytes at offset 16u of each packet) over the workers in `sub`
@@ -274,46 +282,57 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
     return a;
 }
 
-// One block per tile of 64 sequence numbers (one bitmap word per worker), grid-stride over the
-// tiles the batch touched.
-//   phase A  the block's waves split the workers: coalesced read of the arrival index, ballot
-//            -> new bitmap bits (the block owns the words, so plain stores), slots staged in LDS,
-//            index entries reset; one wave computes the 64 packets' element spans in parallel
-//   phase B  the waves split the 64 packets: per packet, 16-byte payload loads from every
+// One block per group of SUB consecutive sequence numbers, grid-stride over the groups the
+// batch touched.
+//   phase A  64 lanes = 4 workers x 16 packets per load of the arrival index: ballot -> new
+//            bitmap bits (one atomicOr per worker and group), slots staged in LDS, index
+//            entries reset; the 16 packets' element spans are computed by 16 lanes in parallel
+//   phase B  the waves split the 16 packets: per packet, 16-byte payload loads from every
 //            worker that delivered it, summed in registers in worker order, one write of the span
 __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
                                                                     u64* __restrict__ pending, u64* __restrict__ bitmap,
                                                                     float* __restrict__ acc, u64* __restrict__ counters) {
-    extern __shared__ u32 sh_slot[];           // [W][64]
-    __shared__ u64 sh_elem[WAVE];
-    __shared__ u32 sh_len[WAVE];
-    __shared__ u64 sh_new[GA_WAVES], sh_old[GA_WAVES];
+    extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB]
+    __shared__ u64 sh_elem[SUB];
+    __shared__ u32 sh_len[SUB];
+    __shared__ u32 sh_new[GA_WAVES], sh_old[GA_WAVES];
     const u64 lo = counters[C_LO], hi = counters[C_HI];
     if (hi == 0) return;                                    // no candidate in this batch
     const u32 lane = lane_id();
     const u32 wave = threadIdx.x / WAVE;
     const u32 W = g.W;
-    const u32 tile_end = (u32)((hi + 63) >> 6);
+    const u32 s_lane = lane & (SUB - 1), w_sub = lane / SUB;   // packet and worker-within-load of this lane
+    const u32 grp_end = (u32)((hi + SUB - 1) / SUB);
     u32 accepted = 0;
 
-    for (u32 tile = (u32)(lo >> 6) + blockIdx.x; tile < tile_end; tile += gridDim.x) {
-        const u32 seq_l = (tile << 6) + lane;
-        const bool valid = seq_l < g.n_pkts;
-        u64 new_or = 0, old_or = 0;
-        for (u32 w = wave; w < W; w += GA_WAVES) {
-            const u64 p = valid ? pending[(u64)w * g.n_pkts + seq_l] : NONE64;
+    for (u32 grp = (u32)(lo / SUB) + blockIdx.x; grp < grp_end; grp += gridDim.x) {
+        const u32 seq0 = grp * SUB;
+        const u32 seq_l = seq0 + s_lane;
+        const u32 word = seq0 >> 6, shift = seq0 & 63;
+        u32 new_or = 0, old_or = 0;
+        for (u32 w0 = wave * 4; w0 < W; w0 += GA_WAVES * 4) {
+            const u32 w = w0 + w_sub;
+            const bool valid = w < W && seq_l < g.n_pkts;
+            u64 p = NONE64, bits = 0;
+            if (valid) {
+                p = pending[(u64)w * g.n_pkts + seq_l];
+                bits = bitmap[(u64)w * g.words_pw + word];
+            }
             const bool has = p != NONE64;
             const u64 nb = __ballot(has);
-            const u64 old = bitmap[(u64)w * g.words_pw + tile];
-            sh_slot[w * WAVE + lane] = has ? (u32)p : NONE32;
-            if (nb) {
-                if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty for the next batch
-                if (lane == 0) bitmap[(u64)w * g.words_pw + tile] = old | nb;
+            sh_slot[w * SUB + s_lane] = has ? (u32)p : NONE32;
+            if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty for the next batch
+            const u32 mine = (u32)(nb >> (w_sub * SUB)) & 0xFFFFu;  // this lane's worker: new bits of the group
+            if (s_lane == 0 && mine) atomicOr(&bitmap[(u64)w * g.words_pw + word], (u64)mine << shift);
+            const u64 ob = __ballot(valid && ((bits >> (shift + s_lane)) & 1ull));
+            #pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                new_or |= (u32)(nb >> (j * SUB)) & 0xFFFFu;
+                old_or |= (u32)(ob >> (j * SUB)) & 0xFFFFu;
             }
-            new_or |= nb; old_or |= old;
             accepted += (u32)__popcll(nb);
         }
-        if (wave == GA_WAVES - 1 && valid) {
+        if (wave == GA_WAVES - 1 && lane < SUB && seq_l < g.n_pkts) {
             const u32 b = find_bucket(g.first_seq, g.B, seq_l);
             u64 elem; u32 len;
             packet_span(g, seq_l, b, &elem, &len);
@@ -321,16 +340,16 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
         }
         if (lane == 0) { sh_new[wave] = new_or; sh_old[wave] = old_or; }
         __syncthreads();
-        u64 new_any = 0, old_any = 0;
+        u32 new_any = 0, old_any = 0;
         #pragma unroll
         for (int i = 0; i < GA_WAVES; ++i) { new_any |= sh_new[i]; old_any |= sh_old[i]; }
 
-        for (u32 t = wave; t < WAVE; t += GA_WAVES) {
-            if (!((new_any >> t) & 1ull)) continue;
-            const bool rmw = (old_any >> t) & 1ull;          // span already holds earlier arrivals
+        for (u32 t = wave; t < SUB; t += GA_WAVES) {
+            if (!((new_any >> t) & 1u)) continue;
+            const bool rmw = (old_any >> t) & 1u;            // span already holds earlier arrivals
             const u64 elem = sh_elem[t];
             const u32 len = sh_len[t];
-            const u32 slot32 = lane < W ? sh_slot[lane * WAVE + t] : NONE32;
+            const u32 slot32 = lane < W ? sh_slot[lane * SUB + t] : NONE32;
             const u64 sub = __ballot(slot32 != NONE32);
             const u32 units = (len + 2 + 3) >> 2;            // 16-byte units holding header + payload
             float* dst0 = acc + elem - 2;                    // float position i of the packet -> dst0[i]
@@ -351,7 +370,7 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
                 }
             }
         }
-        __syncthreads();                                     // LDS is reused by the next tile
+        __syncthreads();                                     // LDS is reused by the next group
     }
     if (lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
 }
@@ -796,9 +815,11 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
     }
     {
         ProfScope ps(c, DBLP_K_GATHER);
-        hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, g.words_pw, 4)), dim3(GA_WAVES * WAVE),
-                           g.W * WAVE * sizeof(u32), c->stream, g, (const uint8_t*)d_packets, c->d_pending,
-                           c->d_bitmap, c->d_acc, c->d_counters);
+        const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
+        const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
+        hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
+                           lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
+                           c->d_counters);
     }
     LAUNCH_CHECK(c, "apply_arrivals");
     c->finalized = 0;
