@@ -215,6 +215,9 @@ def main():
     ap.add_argument("--place", default=None, help="override wire placement: worker_major|interleave|shuffle")
     ap.add_argument("--order", default=None, help="override arrival order: identity|shuffle|reverse")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, "
+                         "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
     ap.add_argument("--cpu-sample-elems", type=int, default=48_000_000)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -239,6 +242,12 @@ def main():
             return 1.0
         return sched[t % len(sched) - 1] / sched[t % len(sched)]
 
+    if args.calibrate_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        b.copy_(a)          # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
     bound = first_bound(w)
     for t in range(args.warmup):
         r = job.step(t, bound, ratio(t))
