@@ -140,7 +140,7 @@ int dblp_loss_account(dblp_ctx* ctx, uint32_t bound_ppm, uint32_t* d_missing, ui
                       uint64_t retx_capacity, uint64_t* h_retx_count, int* h_all_met);
 
 /* Alg. "DBLP_RECV" last statements + Alg. "Server" mean: d_out[e] = acc[e] / W where
- * unreceived chunks count as zero (a span no worker delivered is exactly 0).  d_out: N
+ * unreceived chunks count as zero (a span no worker delivered is exactly 0).  d_out: 16-byte aligned, N
  * floats.  Also accumulates sum(d_out^2) for dblp_phase_signal.  Only
  * DBLP_COMP_ZEROFILL_MEAN is defined by the paper; other values give EINVAL. */
 int dblp_finalize(dblp_ctx* ctx, int compensation, float* d_out);

@@ -375,6 +375,152 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
     if (lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
 }
 
+// Staged variant of the gather (used whenever two groups of packets fit in LDS).
+// Mixing the accumulator stores into the waves that stream the payloads costs far more than the
+// stores' bytes (a payload-only loop sustains 6.2 TB/s on this chip, the same loop with its
+// 3 % of stores 4.9 TB/s).  Here GS_READERS waves only load and add, and hand each summed
+// packet to LDS; one extra writer wave drains the previous group from LDS to the accumulator
+// while the readers work on the next one (double-buffered).  Because the writer reads LDS at
+// arbitrary float offsets, its global accesses are 16-byte aligned float4s whatever the
+// alignment of the packet's element span.
+#ifndef GS_READERS
+#define GS_READERS 8
+#endif
+#ifndef GS_BLOCKS_PER_CU
+#define GS_BLOCKS_PER_CU 3
+#endif
+#define GS_LDS_BUDGET (48u * 1024u)   // bytes for the two packet buffers
+
+__global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_staged(
+    Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
+    float* __restrict__ acc, u64* __restrict__ counters, u32 sub, u32 sub_log2, u32 n_pass) {
+    extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, then slots
+    __shared__ u64 sh_elem[2][SUB];
+    __shared__ u32 sh_len[2][SUB];
+    __shared__ u32 sh_flag_new[2];
+    __shared__ u32 sh_new[GS_READERS], sh_old[GS_READERS];
+    const u64 lo = counters[C_LO], hi = counters[C_HI];
+    if (hi == 0) return;                            // no candidate in this batch (uniform over the grid)
+    const u32 lane = lane_id();
+    const u32 wave = threadIdx.x / WAVE;
+    const u32 W = g.W;
+    const u32 upp = g.stride >> 4;                  // float4 units per packet
+    float4* buf0 = sh_dyn;
+    float4* buf1 = sh_dyn + sub * upp;
+    u32* sh_slot = (u32*)(sh_dyn + 2 * sub * upp);  // [W rounded up to a multiple of 64/sub][sub]
+    const u32 wpl = WAVE >> sub_log2;               // workers per 64-lane load of the index
+    const u32 s_lane = lane & (sub - 1), w_sub = lane >> sub_log2;
+    const u32 submask = (1u << sub) - 1;
+    const u32 grp0 = (u32)(lo >> sub_log2) + blockIdx.x;
+    const u32 grp_end = (u32)((hi + sub - 1) >> sub_log2);
+    const u32 n_it = grp0 < grp_end ? (grp_end - grp0 + gridDim.x - 1) / gridDim.x : 0;
+    u32 accepted = 0;
+
+    for (u32 it = 0; it <= n_it; ++it) {            // one extra turn so the writer drains the last group
+        const u32 cur = it & 1;
+        const u32 seq0 = (grp0 + it * gridDim.x) << sub_log2;
+        if (wave < GS_READERS) {
+            if (it < n_it) {
+                // ---- phase A: arrival index -> bitmap bits, slots, spans
+                const u32 seq_l = seq0 + s_lane;
+                const u32 word = seq0 >> 6, shift = seq0 & 63;
+                u32 new_or = 0, old_or = 0;
+                for (u32 w0 = wave * wpl; w0 < W; w0 += GS_READERS * wpl) {
+                    const u32 w = w0 + w_sub;
+                    const bool valid = w < W && seq_l < g.n_pkts;
+                    u64 p = NONE64, bits = 0;
+                    if (valid) {
+                        p = pending[(u64)w * g.n_pkts + seq_l];
+                        bits = bitmap[(u64)w * g.words_pw + word];
+                    }
+                    const bool has = p != NONE64;
+                    const u64 nb = __ballot(has);
+                    sh_slot[w * sub + s_lane] = has ? (u32)p : NONE32;
+                    if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty
+                    const u32 mine = (u32)(nb >> (w_sub * sub)) & submask;
+                    if (s_lane == 0 && mine) atomicOr(&bitmap[(u64)w * g.words_pw + word], (u64)mine << shift);
+                    const u64 ob = __ballot(valid && ((bits >> (shift + s_lane)) & 1ull));
+                    for (u32 j = 0; j < wpl; ++j) {
+                        new_or |= (u32)(nb >> (j * sub)) & submask;
+                        old_or |= (u32)(ob >> (j * sub)) & submask;
+                    }
+                    accepted += (u32)__popcll(nb);
+                }
+                if (wave == GS_READERS - 1 && lane < sub && seq_l < g.n_pkts) {
+                    const u32 b = find_bucket(g.first_seq, g.B, seq_l);
+                    u64 elem; u32 len;
+                    packet_span(g, seq_l, b, &elem, &len);
+                    sh_elem[cur][lane] = elem; sh_len[cur][lane] = len;
+                }
+                if (lane == 0) { sh_new[wave] = new_or; sh_old[wave] = old_or; }
+            }
+        } else if (it > 0) {
+            // ---- writer: drain group it-1 from LDS to the accumulator (plain aligned stores; a span
+            // that earlier batches had written already has its old value folded in by the readers)
+            const u32 prev = cur ^ 1;
+            const float* src = (const float*)(prev ? buf1 : buf0);
+            const u32 nf = sh_flag_new[prev];
+            for (u32 t = 0; t < sub; ++t) {
+                if (!((nf >> t) & 1u)) continue;
+                const u64 elem = sh_elem[prev][t];
+                const u32 len = sh_len[prev][t];
+                const float* pk = src + t * (g.stride >> 2) + 2;   // payload float j at pk[j]
+                const u64 c0 = elem >> 2, c1 = (elem + len - 1) >> 2;
+                for (u64 c = c0 + lane; c <= c1; c += WAVE) {
+                    const u64 e0 = c << 2;
+                    float* d = acc + e0;
+                    if (e0 >= elem && e0 + 4 <= elem + len) {
+                        const u32 j = (u32)(e0 - elem);
+                        *(float4*)d = make_float4(pk[j], pk[j + 1], pk[j + 2], pk[j + 3]);
+                    } else {
+                        #pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const u64 e = e0 + k;
+                            if (e >= elem && e < elem + len) d[k] = pk[(u32)(e - elem)];
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        if (wave < GS_READERS && it < n_it) {
+            // ---- phase B: payload gather, worker order, results to LDS
+            u32 new_any = 0, old_any = 0;
+            #pragma unroll
+            for (int i = 0; i < GS_READERS; ++i) { new_any |= sh_new[i]; old_any |= sh_old[i]; }
+            if (threadIdx.x == 0) sh_flag_new[cur] = new_any;
+            float4* dstbuf = cur ? buf1 : buf0;
+            const u32 items = n_pass << sub_log2;
+            for (u32 i = wave; i < items; i += GS_READERS) {
+                const u32 t = i & (sub - 1), pass = i >> sub_log2;
+                if (!((new_any >> t) & 1u)) continue;
+                const u32 len = sh_len[cur][t];
+                const u32 units = (len + 2 + 3) >> 2;        // 16-byte units holding header + payload
+                const u32 u = pass * WAVE + lane;
+                if (pass * WAVE >= units) continue;
+                const bool active = u < units;
+                const u32 slot32 = lane < W ? sh_slot[lane * sub + t] : NONE32;
+                const u64 subm = __ballot(slot32 != NONE32);
+                float4 a = sum_unit(packets, g.stride, u, active, subm, slot32);
+                if (active && ((old_any >> t) & 1u)) {
+                    // earlier batches already wrote this span: result = old value + this batch's sum
+                    const float* o = acc + sh_elem[cur][t] - 2 + 4 * u;   // packet float position 4u+c -> o[c]
+                    float q[4] = {a.x, a.y, a.z, a.w};
+                    #pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const u32 i4 = 4 * u + c;
+                        if (i4 >= 2 && i4 - 2 < len) q[c] = o[c] + q[c];
+                    }
+                    a = make_float4(q[0], q[1], q[2], q[3]);
+                }
+                if (active) dstbuf[t * upp + u] = a;
+            }
+        }
+        __syncthreads();
+    }
+    if (wave < GS_READERS && lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
+}
+
 // ------------------------------------------------------------------------------------------
 // probe: per-(worker,bucket) loss count, prefix of list lengths, ordered list
 // ------------------------------------------------------------------------------------------
@@ -470,6 +616,22 @@ __global__ __launch_bounds__(256) void emit_retx(Geo g, const u64* __restrict__ 
 // ------------------------------------------------------------------------------------------
 #define FIN_TILE 8   // consecutive packets per wave step; divides 64 so a tile sits in one bitmap word
 
+// x / P for x < FIN_TILE * P (fits a float exactly enough to be fixed up by one step).
+__device__ __forceinline__ u32 div_small(u32 x, u32 P, float inv_p) {
+    u32 t = (u32)((float)x * inv_p);
+    if (t * P > x) --t;
+    if ((t + 1) * P <= x) ++t;
+    return t;
+}
+
+__device__ __forceinline__ float scale_mean(float v, float inv_w, int use_div, float wf) {
+    return use_div ? v / wf : v * inv_w;
+}
+
+// out = acc / W where some worker delivered the packet, 0 elsewhere; per-block sum of out^2.
+// A tile of 8 packets inside one bucket is one contiguous element range: it is walked in
+// 16-byte aligned chunks (float4 load, scale, float4 store); chunks that straddle a packet or
+// the range's ends, and tiles that cross a bucket boundary, go element by element.
 __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restrict__ bitmap, const float* __restrict__ acc,
                                                      float* __restrict__ out, float inv_w, int use_div, float wf,
                                                      double* __restrict__ partials) {
@@ -479,31 +641,62 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
     const u32 wave = blockIdx.x * (blockDim.x / WAVE) + wave_in_block;
     const u32 n_waves = gridDim.x * (blockDim.x / WAVE);
     const u32 n_tiles = (g.n_pkts + FIN_TILE - 1) / FIN_TILE;
+    const float inv_p = 1.0f / (float)g.P;
     double dsum = 0.0;
     for (u32 tile = wave; tile < n_tiles; tile += n_waves) {
         const u32 seq0 = tile * FIN_TILE;
+        const u32 n_t = g.n_pkts - seq0 < FIN_TILE ? g.n_pkts - seq0 : FIN_TILE;
         u64 any = 0;
         for (u32 w = 0; w < g.W; ++w) any |= bitmap[(u64)w * g.words_pw + (seq0 >> 6)];
         any >>= (seq0 & 63);
         u32 b = find_bucket(g.first_seq, g.B, seq0);
-        for (u32 t = 0; t < FIN_TILE; ++t) {
-            const u32 seq = seq0 + t;
-            if (seq >= g.n_pkts) break;
-            while (seq >= g.first_seq[b + 1]) ++b;
-            u64 elem; u32 len;
-            packet_span(g, seq, b, &elem, &len);
-            float s = 0.f;
-            if ((any >> t) & 1ull) {
-                for (u32 j = lane; j < len; j += WAVE) {
-                    float v = acc[elem + j];
-                    v = use_div ? v / wf : v * inv_w;
-                    out[elem + j] = v;
-                    s += v * v;
+        if (seq0 + n_t <= g.first_seq[b + 1]) {
+            const u64 elem0 = g.b_off[b] + (u64)(seq0 - g.first_seq[b]) * g.P;
+            const u64 bucket_end = g.b_off[b] + g.b_cnt[b];
+            const u64 end = elem0 + (u64)n_t * g.P < bucket_end ? elem0 + (u64)n_t * g.P : bucket_end;
+            const u64 c1 = (end - 1) >> 2;
+            for (u64 c = (elem0 >> 2) + lane; c <= c1; c += WAVE) {
+                const u64 e0 = c << 2;
+                const u64 lo_e = e0 > elem0 ? e0 : elem0, hi_e = e0 + 3 < end - 1 ? e0 + 3 : end - 1;
+                const u32 t_lo = div_small((u32)(lo_e - elem0), g.P, inv_p), t_hi = div_small((u32)(hi_e - elem0), g.P, inv_p);
+                if (e0 >= elem0 && e0 + 4 <= end && t_lo == t_hi) {
+                    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);      // never received: exactly zero
+                    if ((any >> t_lo) & 1ull) {
+                        v = *(const float4*)(acc + e0);
+                        v.x = scale_mean(v.x, inv_w, use_div, wf); v.y = scale_mean(v.y, inv_w, use_div, wf);
+                        v.z = scale_mean(v.z, inv_w, use_div, wf); v.w = scale_mean(v.w, inv_w, use_div, wf);
+                        dsum += (double)((v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w));
+                    }
+                    *(float4*)(out + e0) = v;
+                } else {
+                    for (u64 e = lo_e; e <= hi_e; ++e) {
+                        float v = 0.f;
+                        if ((any >> div_small((u32)(e - elem0), g.P, inv_p)) & 1ull) {
+                            v = scale_mean(acc[e], inv_w, use_div, wf);
+                            dsum += (double)(v * v);
+                        }
+                        out[e] = v;
+                    }
                 }
-            } else {
-                for (u32 j = lane; j < len; j += WAVE) out[elem + j] = 0.f;   // never received: exactly zero
             }
-            dsum += (double)s;
+        } else {
+            for (u32 t = 0; t < n_t; ++t) {
+                const u32 seq = seq0 + t;
+                while (seq >= g.first_seq[b + 1]) ++b;
+                u64 elem; u32 len;
+                packet_span(g, seq, b, &elem, &len);
+                float s = 0.f;
+                if ((any >> t) & 1ull) {
+                    for (u32 j = lane; j < len; j += WAVE) {
+                        const float v = scale_mean(acc[elem + j], inv_w, use_div, wf);
+                        out[elem + j] = v;
+                        s += v * v;
+                    }
+                } else {
+                    for (u32 j = lane; j < len; j += WAVE) out[elem + j] = 0.f;
+                }
+                dsum += (double)s;
+            }
         }
     }
     dsum = wave_sum_f64(dsum);
@@ -815,11 +1008,23 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
     }
     {
         ProfScope ps(c, DBLP_K_GATHER);
-        const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
-        const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
-        hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
-                           lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
-                           c->d_counters);
+        u32 sub = SUB, sub_log2 = 4;
+        while (sub >= 2 && 2u * sub * g.stride > GS_LDS_BUDGET) { sub >>= 1; --sub_log2; }
+        if (sub >= 2) {   // two groups of packets fit in LDS: readers + writer wave
+            const u32 wpl = WAVE / sub;
+            const size_t lds = 2ull * sub * g.stride + (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
+            const u64 groups = ((u64)g.n_pkts + sub - 1) / sub;
+            hipLaunchKernelGGL(gather_accumulate_staged, dim3(grid_for(c, groups, GS_BLOCKS_PER_CU)),
+                               dim3((GS_READERS + 1) * WAVE), lds, c->stream, g, (const uint8_t*)d_packets,
+                               c->d_pending, c->d_bitmap, c->d_acc, c->d_counters, sub, sub_log2,
+                               (g.units + WAVE - 1) / WAVE);
+        } else {          // very long packets: direct stores from the gathering waves
+            const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
+            const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
+            hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
+                               lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
+                               c->d_counters);
+        }
     }
     LAUNCH_CHECK(c, "apply_arrivals");
     c->finalized = 0;
@@ -859,6 +1064,7 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
     if (!c->round_open) return fail(c, DBLP_ESTATE, "finalize before begin_round");
     if (compensation != DBLP_COMP_ZEROFILL_MEAN) return fail(c, DBLP_EINVAL, "finalize: unknown compensation mode");
     if (!d_out) return fail(c, DBLP_EINVAL, "finalize: null output");
+    if (((uintptr_t)d_out & 15) != 0) return fail(c, DBLP_EINVAL, "finalize: d_out must be 16-byte aligned");
     HIP_TRY(c, hipSetDevice(c->device));
     const Geo& g = c->g;
     const u32 W = g.W;
