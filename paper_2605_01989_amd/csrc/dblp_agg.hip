@@ -391,6 +391,42 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
 #endif
 #define GS_LDS_BUDGET (48u * 1024u)   // bytes for the two packet buffers
 
+// Sum of one whole packet over the workers in `sub`: lane l holds 16-byte units l, l+64, ...
+// (NP of them).  All NP loads of one worker's packet are issued together, so a packet's
+// cache lines are requested back to back (a line shared by two 1 KB passes is fetched once),
+// and 8/NP workers (at least 2) are in flight at a time.  Same addition order as sum_unit.
+template <int NP>
+__device__ __forceinline__ void sum_packet(const uint8_t* __restrict__ packets, u32 stride, u32 lane, u32 units,
+                                           u64 sub, u32 slot32, float4 (&a)[NP]) {
+    constexpr int G = NP <= 2 ? 8 / NP : 2;
+    #pragma unroll
+    for (int q = 0; q < NP; ++q) a[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    while (sub) {
+        float4 v[G][NP];
+        #pragma unroll
+        for (int j = 0; j < G; ++j) {
+            #pragma unroll
+            for (int q = 0; q < NP; ++q) v[j][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (sub) {
+                const u32 w = (u32)__builtin_ctzll(sub);
+                sub &= sub - 1;
+                const u32 slot = (u32)__builtin_amdgcn_readlane((int)slot32, (int)w);
+                const uint8_t* base = packets + (u64)slot * stride + 16ull * lane;
+                #pragma unroll
+                for (int q = 0; q < NP; ++q)
+                    if (q * WAVE + lane < units) v[j][q] = *(const float4*)(base + 1024ull * q);
+            }
+        }
+        #pragma unroll
+        for (int j = 0; j < G; ++j) {
+            #pragma unroll
+            for (int q = 0; q < NP; ++q) { a[q].x += v[j][q].x; a[q].y += v[j][q].y; a[q].z += v[j][q].z; a[q].w += v[j][q].w; }
+        }
+    }
+}
+
+// NP = 16-byte-unit passes per packet handled in one go (1..5), 0 = generic one pass at a time.
+template <int NP>
 __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_staged(
     Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
     float* __restrict__ acc, u64* __restrict__ counters, u32 sub, u32 sub_log2, u32 n_pass) {
@@ -490,6 +526,35 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
             for (int i = 0; i < GS_READERS; ++i) { new_any |= sh_new[i]; old_any |= sh_old[i]; }
             if (threadIdx.x == 0) sh_flag_new[cur] = new_any;
             float4* dstbuf = cur ? buf1 : buf0;
+            if (NP > 0) {
+                for (u32 t = wave; t < sub; t += GS_READERS) {
+                    if (!((new_any >> t) & 1u)) continue;
+                    const u32 len = sh_len[cur][t];
+                    const u32 units = (len + 2 + 3) >> 2;        // 16-byte units holding header + payload
+                    const u32 slot32 = lane < W ? sh_slot[lane * sub + t] : NONE32;
+                    const u64 subm = __ballot(slot32 != NONE32);
+                    float4 a[NP > 0 ? NP : 1];
+                    sum_packet<(NP > 0 ? NP : 1)>(packets, g.stride, lane, units, subm, slot32, a);
+                    const bool rmw = (old_any >> t) & 1u;         // earlier batches already wrote this span
+                    #pragma unroll
+                    for (int q = 0; q < (NP > 0 ? NP : 1); ++q) {
+                        const u32 u = q * WAVE + lane;
+                        if (u >= units) continue;
+                        float4 r = a[q];
+                        if (rmw) {                                // result = old value + this batch's sum
+                            const float* o = acc + sh_elem[cur][t] - 2 + 4 * u;   // packet float position 4u+c -> o[c]
+                            float qv[4] = {r.x, r.y, r.z, r.w};
+                            #pragma unroll
+                            for (int c = 0; c < 4; ++c) {
+                                const u32 i4 = 4 * u + c;
+                                if (i4 >= 2 && i4 - 2 < len) qv[c] = o[c] + qv[c];
+                            }
+                            r = make_float4(qv[0], qv[1], qv[2], qv[3]);
+                        }
+                        dstbuf[t * upp + u] = r;
+                    }
+                }
+            } else {
             const u32 items = n_pass << sub_log2;
             for (u32 i = wave; i < items; i += GS_READERS) {
                 const u32 t = i & (sub - 1), pass = i >> sub_log2;
@@ -514,6 +579,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                     a = make_float4(q[0], q[1], q[2], q[3]);
                 }
                 if (active) dstbuf[t * upp + u] = a;
+            }
             }
         }
         __syncthreads();
@@ -1014,10 +1080,14 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
             const u32 wpl = WAVE / sub;
             const size_t lds = 2ull * sub * g.stride + (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
             const u64 groups = ((u64)g.n_pkts + sub - 1) / sub;
-            hipLaunchKernelGGL(gather_accumulate_staged, dim3(grid_for(c, groups, GS_BLOCKS_PER_CU)),
-                               dim3((GS_READERS + 1) * WAVE), lds, c->stream, g, (const uint8_t*)d_packets,
-                               c->d_pending, c->d_bitmap, c->d_acc, c->d_counters, sub, sub_log2,
-                               (g.units + WAVE - 1) / WAVE);
+            const u32 n_pass = (g.units + WAVE - 1) / WAVE;
+            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, u64*, u32, u32, u32) =
+                n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
+                : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
+                : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
+            hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, GS_BLOCKS_PER_CU)), dim3((GS_READERS + 1) * WAVE),
+                               lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
+                               c->d_counters, sub, sub_log2, n_pass);
         } else {          // very long packets: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
             const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);

@@ -70,6 +70,10 @@ CASES = [
     (7, [256 * 130], 256, 0.01, 0),
     (3, [4_000_000], 1000, 0.01, 8_000),                                     # one bucket = whole-round accounting
     (2, [65535 * 3 + 1], 65535, 0.0, 0),                                     # maximum packet length
+    (4, [600 * 40 + 7, 100], 600, 0.05, 30_000),                             # three 1 KB passes per packet
+    (3, [1400 * 33 + 5], 1400, 0.05, 30_000),                                # six passes: generic staged path
+    (2, [3000 * 9 + 1], 3000, 0.1, 50_000),                                  # 12 KB packets: two-packet groups
+    (2, [4000 * 5 + 3], 4000, 0.1, 50_000),                                  # too long to stage: direct stores
 ]
 
 
