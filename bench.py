@@ -129,10 +129,11 @@ class DeviceJob:
         return dict(words=out, lost=int(surv.size - int(surv.sum())))
 
     # -- the timed path --------------------------------------------------------------------
-    def step(self, it: int, bound_ppm: int, scale_ratio: float = 1.0) -> dict:
+    def step(self, it: int, bound_ppm: int, scale_ratio: float = 1.0, record: list | None = None) -> dict:
         """One iteration.  scale_ratio = s_{t-1}/s_t of the workload's gradient-scale schedule:
         the resident gradient is not rescaled between steps, so the previous norm is rescaled
-        instead, which gives Eq. 1 the same relative change."""
+        instead, which gives Eq. 1 the same relative change.  With `record` (a list) every
+        probe's per-bucket counts and retransmit list are copied to the host and appended."""
         torch, agg, L = self.torch, self.agg, self.L
         st = L.stride
         m = self.masks[it % len(self.masks)]
@@ -145,6 +146,10 @@ class DeviceJob:
             count, met, trunc = agg.loss_account(bound_ppm, self.d_missing, self.d_list)
             if trunc:
                 raise RuntimeError(f"retransmit list ({count}) exceeds its buffer ({self.list_cap})")
+            if record is not None:
+                record.append(dict(count=count, met=met,
+                                   missing=self.d_missing.cpu().numpy().view(np.uint32).reshape(L.W, L.B).copy(),
+                                   list=self.d_list[:count].cpu().numpy().view(np.uint64).copy()))
             if met:
                 break
             rounds += 1
@@ -161,8 +166,7 @@ class DeviceJob:
         if prev is not None:
             agg.set_prev_norm(prev * scale_ratio)
         norm, delta, crit = agg.phase_signal()
-        return dict(rounds=rounds, resent=resent, norm=norm, rel_delta=delta, critical=crit,
-                    lost_first=m["lost"], list_first=None)
+        return dict(rounds=rounds, resent=resent, norm=norm, rel_delta=delta, critical=crit, lost_first=m["lost"])
 
 
 def next_bound(w, rel_delta: float, critical: bool) -> int:

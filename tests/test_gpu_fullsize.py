@@ -1,0 +1,138 @@
+"""Parity at full size, in the configuration bench.py times: the 1.3B-element, W=32 workload with
+every packet of a round resident in HBM (167 GB), chunk-streamed application, shuffled placement
+and arrival order, burst loss, a 2 % bound with retransmission rounds.
+
+The oracle cannot run 113.7 M packets' payloads in seconds, so it computes sampled outputs one by
+one: for a sample of buckets it is given exactly that bucket's packets, in their original relative
+arrival order, and must reproduce the GPU's per-(worker, bucket) counts, retransmit-list entries,
+bitmap bits and aggregated elements for that bucket (loss accounting and aggregation are
+independent across buckets, so a bucket is an exact sub-problem).  Properties that hold at any size
+cover the rest: total missing = packets - accepted, no spurious stale/invalid/duplicate counts, and
+the norm of the returned gradient."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+BOUND_PPM = 20_000
+
+
+_SURVIVE = {}
+
+
+def survive(job, rnd):
+    if rnd not in _SURVIVE:
+        _SURVIVE[rnd] = job.w.survive(0, rnd, job.slot_of)
+    return _SURVIVE[rnd]
+
+
+def bucket_subproblem(job, b, probes, bound_ppm):
+    """Run the oracle on bucket b alone; compare with what the GPU reported for it."""
+    import oracle
+    from harness import FLOAT_TOL
+    w, L = job.w, job.L
+    s0, s1 = int(L.first_seq[b]), int(L.first_seq[b + 1])
+    e0, cnt = int(L.bucket_off[b]), int(L.bucket_cnt[b])
+    n = s1 - s0
+    ch = next(c for c in job.chunks if c["s0"] <= s0 < c["s1"])
+    ci = job.chunks.index(ch)
+    # this bucket's packets in their original relative arrival order
+    gslots = job.slot_of[:, s0:s1].astype(np.int64)                       # [W, n] global slots
+    local = gslots - ch["base"]
+    order = wl.arrival_order(job.order, ch["n"], w.seed, ci)
+    rank = np.arange(ch["n"], dtype=np.int64)
+    if order is not None:
+        rank[order.astype(np.int64)] = np.arange(ch["n"])
+    by_rank = np.argsort(rank[local.reshape(-1)], kind="stable")          # sub-stream arrival order
+    o = oracle.Oracle(L.W, cnt, L.P, [0], [cnt], w.policy.get("eta", 0.5))
+    assert o.n_pkts == n
+    packets = np.zeros(L.W * n * L.stride, dtype=np.uint8)
+    src = np.zeros(L.W * n, dtype=np.uint16)
+    grads = []
+    for wk in range(L.W):
+        g = wl.grad_values(w.seed, wk, 0, e0, cnt, w.sigma_at(0), w.tail_ppm, w.tail_mul)
+        grads.append(g)
+        o.packetize(wk, job.rnd_id, g, 0, 0, n, packets, src, slot_base=wk * n)   # sub-slot = wk*n + seq
+    survive0 = survive(job, 0)[:, s0:s1]
+    mask = np.packbits(np.pad(survive0.reshape(-1), (0, (-L.W * n) % 64)), bitorder="little").view(np.uint64)
+    o.begin_round(job.rnd_id)
+    o.apply_arrivals(packets, src, L.W * n, mask, by_rank.astype(np.uint32))
+    rnd = 0
+    for pr in probes:
+        missing, lst, count, met = o.loss_account(bound_ppm)
+        assert np.array_equal(missing[:, 0], pr["missing"][:, b]), f"bucket {b}: missing counts differ at probe {rnd}"
+        gl = pr["list"]
+        gseq = (gl & np.uint64(0xFFFFFFFF)).astype(np.int64)
+        mine = gl[(gseq >= s0) & (gseq < s1)]
+        want = (lst & ~np.uint64(0xFFFFFFFF)) | ((lst & np.uint64(0xFFFFFFFF)) + np.uint64(s0))
+        assert np.array_equal(mine, want), f"bucket {b}: retransmit entries differ at probe {rnd}"
+        if pr["met"]:
+            break
+        rnd += 1
+        if not met:   # resend this bucket's listed packets; the drawn loss of round rnd applies
+            ws = (lst >> np.uint64(32)).astype(np.int64)
+            ss = (lst & np.uint64(0xFFFFFFFF)).astype(np.int64)
+            if rnd in job.d_survive:
+                ok = survive(job, rnd)[ws, ss + s0].astype(bool)
+                ws, ss = ws[ok], ss[ok]
+            o.apply_arrivals(packets, src, L.W * n, None, (ws * n + ss).astype(np.uint32))
+    rec = o.received()
+    ref = o.finalize()
+    got = job.d_out[e0:e0 + cnt].cpu().numpy().astype(np.float64)
+    pkt = np.arange(cnt) // L.P
+    scale = sum(rec[wk, pkt] * np.abs(grads[wk].astype(np.float64)) for wk in range(L.W)) / L.W
+    zero = scale == 0
+    assert np.all(got[zero] == 0.0)
+    rel = (np.abs(got - ref)[~zero] / scale[~zero]).max()
+    assert rel <= FLOAT_TOL, f"bucket {b}: float parity {rel:.3e}"
+    return rec, rel
+
+
+def test_cfg5_full_size_sampled_buckets_and_global_properties():
+    import torch
+    import bench
+    w = wl.workload("cfg5")
+    job = bench.DeviceJob(w, n_masks=1)
+    L = job.L
+    probes = []
+    res = job.step(0, BOUND_PPM, record=probes)
+    counters = job.agg.get_counters()
+    # --- properties that hold at any size
+    assert counters["stale"] == 0 and counters["invalid"] == 0 and counters["duplicate"] == 0
+    assert res["rounds"] >= 1 and probes[-1]["met"] and not probes[0]["met"]
+    assert int(probes[-1]["missing"].astype(np.int64).sum()) == L.W * L.n_pkts - counters["accepted"]
+    allowed = (BOUND_PPM * L.n_b.astype(np.int64)) // 1_000_000
+    assert np.all(probes[-1]["missing"] <= allowed[None, :])            # every bucket meets the bound
+    first = probes[0]
+    fails = first["missing"] > allowed[None, :]
+    assert first["count"] == int(first["missing"][fails].astype(np.int64).sum())
+    lst = first["list"]
+    assert np.all(lst[1:] > lst[:-1])                                   # sorted, no repeats
+    ss = torch.zeros((), dtype=torch.float64, device="cuda")
+    for i in range(0, L.N, 1 << 27):
+        ss += job.d_out[i:i + (1 << 27)].double().square().sum()
+    ref_norm = float(ss.sqrt())
+    assert abs(res["norm"] - ref_norm) <= 1e-6 * ref_norm
+    # --- sampled buckets against the oracle
+    bitmap = torch.empty(L.W * job.agg.words_pw, dtype=torch.int64, device="cuda")
+    job.agg.get_bitmap(bitmap)
+    words = bitmap.cpu().numpy().view(np.uint64).reshape(L.W, job.agg.words_pw)
+    rng = np.random.default_rng(2605)
+    sample = sorted({0, 43, 44, L.B - 2, L.B - 1, *rng.integers(1, L.B - 2, size=7).tolist()})
+    worst = 0.0
+    for b in sample:
+        rec, rel = bucket_subproblem(job, b, probes, BOUND_PPM)
+        s0, s1 = int(L.first_seq[b]), int(L.first_seq[b + 1])
+        seqs = np.arange(s0, s1)
+        gbits = (words[:, seqs >> 6] >> (seqs & 63).astype(np.uint64)) & np.uint64(1)
+        assert np.array_equal(gbits.astype(np.uint8), rec), f"bucket {b}: bitmap differs"
+        worst = max(worst, rel)
+    print(f"cfg5 full size: rounds={res['rounds']} first list={first['count']} accepted={counters['accepted']} "
+          f"sampled buckets={sample} worst float rel={worst:.2e}")
+    _SURVIVE.clear()
+    del job, bitmap
+    torch.cuda.empty_cache()
