@@ -36,7 +36,7 @@ typedef uint32_t u32;
 #define WAVE 64
 
 // device counters (u64 each)
-enum { C_ACCEPTED = 0, C_DUP_PREV, C_STALE, C_INVALID, C_CANDIDATES, C_LO, C_HI, C_PKT_BAD, C_COUNT };
+enum { C_ACCEPTED = 0, C_UNUSED, C_STALE, C_INVALID, C_CANDIDATES, C_LO, C_HI, C_PKT_BAD, C_COUNT };
 
 struct Geo {
     const u32* first_seq;   // [B+1]
@@ -189,10 +189,10 @@ __global__ __launch_bounds__(256) void packetize_kernel(Geo g, u32 w, u32 round,
 __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __restrict__ packets,
                                                       const uint16_t* __restrict__ src_worker, u64 n_slots,
                                                       const u64* __restrict__ mask, const u32* __restrict__ order,
-                                                      u64 n_arrivals, u32 cur_round, const u64* __restrict__ bitmap,
-                                                      u64* __restrict__ pending, u64* __restrict__ counters) {
+                                                      u64 n_arrivals, u32 cur_round, u64* __restrict__ pending,
+                                                      u64* __restrict__ counters) {
     __shared__ u32 sh[4][6];
-    u32 n_stale = 0, n_inv = 0, n_dup = 0, n_cand = 0;
+    u32 n_stale = 0, n_inv = 0, n_cand = 0;
     u32 seq_lo = 0xFFFFFFFFu, seq_hi = 0;
     const u64 stride = (u64)gridDim.x * blockDim.x;
     for (u64 k = (u64)blockIdx.x * blockDim.x + threadIdx.x; k < n_arrivals; k += stride) {
@@ -208,7 +208,6 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
         u64 elem; u32 want;
         packet_span(g, seq, b, &elem, &want);
         if (len != want) { ++n_inv; continue; }
-        if ((bitmap[(u64)w * g.words_pw + (seq >> 6)] >> (seq & 63)) & 1ull) { ++n_dup; continue; }   // earlier batch
         ++n_cand;
         atomicMin(&pending[(u64)w * g.n_pkts + seq], (k << 32) | slot);
         seq_lo = seq < seq_lo ? seq : seq_lo;
@@ -216,11 +215,11 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
     }
     // loops above have lane-dependent trip counts; all 64 lanes are back here
     n_stale = wave_reduce<OpAdd>(n_stale); n_inv = wave_reduce<OpAdd>(n_inv);
-    n_dup = wave_reduce<OpAdd>(n_dup); n_cand = wave_reduce<OpAdd>(n_cand);
+    n_cand = wave_reduce<OpAdd>(n_cand);
     seq_lo = wave_reduce<OpMin>(seq_lo); seq_hi = wave_reduce<OpMax>(seq_hi);
     const u32 wave = threadIdx.x / WAVE;
     if (lane_id() == 0) {
-        sh[wave][0] = n_stale; sh[wave][1] = n_inv; sh[wave][2] = n_dup; sh[wave][3] = n_cand;
+        sh[wave][0] = n_stale; sh[wave][1] = n_inv; sh[wave][2] = 0; sh[wave][3] = n_cand;
         sh[wave][4] = seq_lo; sh[wave][5] = seq_hi;
     }
     __syncthreads();
@@ -233,7 +232,6 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
         }
         if (t[0]) atomicAdd(&counters[C_STALE], (u64)t[0]);
         if (t[1]) atomicAdd(&counters[C_INVALID], (u64)t[1]);
-        if (t[2]) atomicAdd(&counters[C_DUP_PREV], (u64)t[2]);
         if (t[3]) {
             atomicAdd(&counters[C_CANDIDATES], (u64)t[3]);
             // the range only widens: skip the atomic when a plain read shows it would not
@@ -319,12 +317,14 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
                 bits = bitmap[(u64)w * g.words_pw + word];
             }
             const bool has = p != NONE64;
-            const u64 nb = __ballot(has);
-            sh_slot[w * SUB + s_lane] = has ? (u32)p : NONE32;
+            const bool had = valid && ((bits >> (shift + s_lane)) & 1ull);   // delivered by an earlier batch
+            const bool fresh = has && !had;                                  // a copy of a delivered packet is dropped
+            const u64 nb = __ballot(fresh);
+            sh_slot[w * SUB + s_lane] = fresh ? (u32)p : NONE32;
             if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty for the next batch
             const u32 mine = (u32)(nb >> (w_sub * SUB)) & 0xFFFFu;  // this lane's worker: new bits of the group
             if (s_lane == 0 && mine) atomicOr(&bitmap[(u64)w * g.words_pw + word], (u64)mine << shift);
-            const u64 ob = __ballot(valid && ((bits >> (shift + s_lane)) & 1ull));
+            const u64 ob = __ballot(had);
             #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 new_or |= (u32)(nb >> (j * SUB)) & 0xFFFFu;
@@ -470,12 +470,14 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                         bits = bitmap[(u64)w * g.words_pw + word];
                     }
                     const bool has = p != NONE64;
-                    const u64 nb = __ballot(has);
-                    sh_slot[w * sub + s_lane] = has ? (u32)p : NONE32;
+                    const bool had = valid && ((bits >> (shift + s_lane)) & 1ull);   // delivered by an earlier batch
+                    const bool fresh = has && !had;                     // a copy of a delivered packet is dropped
+                    const u64 nb = __ballot(fresh);
+                    sh_slot[w * sub + s_lane] = fresh ? (u32)p : NONE32;
                     if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty
                     const u32 mine = (u32)(nb >> (w_sub * sub)) & submask;
                     if (s_lane == 0 && mine) atomicOr(&bitmap[(u64)w * g.words_pw + word], (u64)mine << shift);
-                    const u64 ob = __ballot(valid && ((bits >> (shift + s_lane)) & 1ull));
+                    const u64 ob = __ballot(had);
                     for (u32 j = 0; j < wpl; ++j) {
                         new_or |= (u32)(nb >> (j * sub)) & submask;
                         old_or |= (u32)(ob >> (j * sub)) & submask;
@@ -1070,7 +1072,7 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
         ProfScope ps(c, DBLP_K_INDEX);
         hipLaunchKernelGGL(index_arrivals, dim3(grid_for(c, (n_arrivals + 255) / 256, 8)), dim3(256), 0, c->stream, g,
                            (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
-                           (u64)n_arrivals, (u32)c->round, c->d_bitmap, c->d_pending, c->d_counters);
+                           (u64)n_arrivals, (u32)c->round, c->d_pending, c->d_counters);
     }
     {
         ProfScope ps(c, DBLP_K_GATHER);
@@ -1200,7 +1202,7 @@ extern "C" int dblp_get_counters(dblp_ctx* c, uint64_t h[4]) {
     HIP_TRY(c, hipMemcpyAsync(tmp, c->d_counters, sizeof tmp, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     h[0] = tmp[C_ACCEPTED];
-    h[1] = tmp[C_DUP_PREV] + (tmp[C_CANDIDATES] - tmp[C_ACCEPTED]);   // earlier batches + second copies in a batch
+    h[1] = tmp[C_CANDIDATES] - tmp[C_ACCEPTED];   // valid arrivals that were not the first copy of their packet
     h[2] = tmp[C_STALE];
     h[3] = tmp[C_INVALID];
     return DBLP_OK;
