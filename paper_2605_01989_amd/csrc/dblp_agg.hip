@@ -36,7 +36,7 @@ typedef uint32_t u32;
 #define WAVE 64
 
 // device counters (u64 each)
-enum { C_ACCEPTED = 0, C_UNUSED, C_STALE, C_INVALID, C_CANDIDATES, C_LO, C_HI, C_PKT_BAD, C_COUNT };
+enum { C_ACCEPTED = 0, C_BATCH_CAND, C_STALE, C_INVALID, C_CANDIDATES, C_LO, C_HI, C_PKT_BAD, C_COUNT };
 
 struct Geo {
     const u32* first_seq;   // [B+1]
@@ -139,7 +139,7 @@ __global__ void reset_counters(u64* __restrict__ c, int keep_round_totals) {
     u32 t = threadIdx.x;
     if (t >= C_COUNT) return;
     if (t == C_LO) c[t] = NONE64;
-    else if (t == C_HI) c[t] = 0;
+    else if (t == C_HI || t == C_BATCH_CAND) c[t] = 0;
     else if (!keep_round_totals) c[t] = 0;
 }
 
@@ -234,6 +234,7 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
         if (t[1]) atomicAdd(&counters[C_INVALID], (u64)t[1]);
         if (t[3]) {
             atomicAdd(&counters[C_CANDIDATES], (u64)t[3]);
+            atomicAdd(&counters[C_BATCH_CAND], (u64)t[3]);
             // the range only widens: skip the atomic when a plain read shows it would not
             if ((u64)lo < *(volatile u64*)&counters[C_LO]) atomicMin(&counters[C_LO], (u64)lo);
             if ((u64)hi > *(volatile u64*)&counters[C_HI]) atomicMax(&counters[C_HI], (u64)hi);
@@ -255,6 +256,16 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
 #endif
 #define SUB 16              // consecutive sequence numbers a block handles at a time (divides 64)
 #define NONE32 0xFFFFFFFFu
+
+// A batch is sparse when it holds fewer than one packet per SPARSE_DIV (worker, seq) pairs of the
+// sequence range it touches (retransmission batches).  Sparse batches take the direct kernel
+// (independent waves, no staging pipeline to fill per group), dense ones the staged kernel; both
+// are launched and the one whose regime it is not returns at once.
+#define SPARSE_DIV 8
+__device__ __forceinline__ bool batch_is_sparse(const u64* counters, u32 W) {
+    const u64 lo = counters[C_LO], hi = counters[C_HI];
+    return counters[C_BATCH_CAND] * SPARSE_DIV < (hi - lo) * W;
+}
 
 // Sum the payload unit `u` (16 bytes at offset 16u of each packet) over the workers in `sub`
 // (bit w set = worker w delivered this packet in this batch), ascending worker order.
@@ -289,13 +300,15 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
 //            worker that delivered it, summed in registers in worker order, one write of the span
 __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
                                                                     u64* __restrict__ pending, u64* __restrict__ bitmap,
-                                                                    float* __restrict__ acc, u64* __restrict__ counters) {
+                                                                    float* __restrict__ acc, u64* __restrict__ counters,
+                                                                    int only_if_sparse) {
     extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB]
     __shared__ u64 sh_elem[SUB];
     __shared__ u32 sh_len[SUB];
     __shared__ u32 sh_new[GA_WAVES], sh_old[GA_WAVES];
     const u64 lo = counters[C_LO], hi = counters[C_HI];
     if (hi == 0) return;                                    // no candidate in this batch
+    if (only_if_sparse && !batch_is_sparse(counters, g.W)) return;
     const u32 lane = lane_id();
     const u32 wave = threadIdx.x / WAVE;
     const u32 W = g.W;
@@ -437,6 +450,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
     __shared__ u32 sh_new[GS_READERS], sh_old[GS_READERS];
     const u64 lo = counters[C_LO], hi = counters[C_HI];
     if (hi == 0) return;                            // no candidate in this batch (uniform over the grid)
+    if (batch_is_sparse(counters, g.W)) return;     // left to the direct kernel
     const u32 lane = lane_id();
     const u32 wave = threadIdx.x / WAVE;
     const u32 W = g.W;
@@ -1090,12 +1104,13 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
             hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, GS_BLOCKS_PER_CU)), dim3((GS_READERS + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
                                c->d_counters, sub, sub_log2, n_pass);
-        } else {          // very long packets: direct stores from the gathering waves
+        }
+        {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
             const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
             hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
-                               c->d_counters);
+                               c->d_counters, sub >= 2 ? 1 : 0);
         }
     }
     LAUNCH_CHECK(c, "apply_arrivals");
