@@ -48,7 +48,10 @@ class DeviceJob:
     """One workload with every input resident in HBM, driven through the C-ABI binding."""
 
     def __init__(self, w, n_masks: int, place: str | None = None, order: str | None = None,
-                 drawn_rounds: int = BENCH_DRAWN_ROUNDS):
+                 drawn_rounds: int = BENCH_DRAWN_ROUNDS, per_iteration_retx: bool = False):
+        """drawn_rounds: retransmission rounds whose loss is drawn once (keyed to iteration 0) and kept
+        on the device.  per_iteration_retx: draw every retransmission round's loss for the iteration
+        at hand instead (small workloads whose loss process depends on the iteration)."""
         import torch
         import paper_2605_01989_amd as dblp
         import workloads as wl
@@ -81,7 +84,8 @@ class DeviceJob:
         # first-transmission masks per step, retransmission survival per drawn round
         self.masks = [self._mask_for(it) for it in range(n_masks)]
         self.d_survive = {}
-        for r in range(1, drawn_rounds + 1):
+        self.per_iteration_retx = per_iteration_retx
+        for r in range(1, 0 if per_iteration_retx else drawn_rounds + 1):
             s = w.survive(0, r, self.slot_of)
             self.d_survive[r] = torch.from_numpy(s.reshape(-1)).to(dev)
         torch.cuda.synchronize()
@@ -156,7 +160,10 @@ class DeviceJob:
             # the simulated sender + network: resend the listed packets, redraw their loss
             lst = self.d_list[:count]
             idx = (lst >> 32) * L.n_pkts + (lst & 0xFFFFFFFF)
-            if rounds in self.d_survive:
+            if self.per_iteration_retx and rounds <= self.w.drawn_rounds:
+                d_s = torch.from_numpy(self.w.survive(it, rounds, self.slot_of).reshape(-1)).cuda()
+                idx = idx[d_s[idx].bool()]
+            elif rounds in self.d_survive:
                 idx = idx[self.d_survive[rounds][idx].bool()]
             slots = self.d_slot_of[idx]
             resent += int(slots.numel())

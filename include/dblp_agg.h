@@ -190,6 +190,22 @@ uint32_t dblp_policy_three_level(double rel_delta, double eta, uint32_t tight_pp
                                  uint32_t loose_ppm);
 uint32_t dblp_policy_linear(double rel_delta, double eta, uint32_t lo_ppm, uint32_t hi_ppm);
 
+/* Epoch-level tolerance controller, Alg. "Server" (the tolerance block inside the loop) and Sec.
+ * "Centralized All-Reduce Architecture": the threshold starts at P_low; at the first
+ * iteration of every epoch it is reset to P_high and, if that iteration's gradient triggers
+ * critical-regime detection (Eq. 1), set to P_low; inside an epoch it does not change.
+ * The caller owns the state (plain struct, host memory).  dblp_clr_init sets bound_ppm = P_low;
+ * dblp_clr_step is called once per iteration, after dblp_phase_signal, with that iteration's
+ * `critical` flag, and returns the bound for the following iterations (also left in
+ * state->bound_ppm).  iters_per_epoch must be >= 1. */
+typedef struct {
+    uint32_t p_low_ppm, p_high_ppm, iters_per_epoch;
+    uint32_t bound_ppm; /* tolerance currently in force */
+    uint64_t step;      /* iterations seen so far */
+} dblp_clr_state;
+int dblp_clr_init(dblp_clr_state* state, uint32_t p_low_ppm, uint32_t p_high_ppm, uint32_t iters_per_epoch);
+uint32_t dblp_clr_step(dblp_clr_state* state, int critical);
+
 #ifdef __cplusplus
 }
 #endif

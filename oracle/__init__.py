@@ -53,6 +53,7 @@ def lib():
         L.oracle_policy_three_level.argtypes = [dbl, dbl, u32, u32, u32]
         L.oracle_policy_linear.restype = u32
         L.oracle_policy_linear.argtypes = [dbl, dbl, u32, u32]
+        L.oracle_clr_trace.argtypes = [u32, u32, u32, vp, u64, vp]
         _lib = L
     return _lib
 
@@ -162,3 +163,11 @@ def policy_three_level(rel_delta: float, eta: float, tight_ppm: int, mid_ppm: in
 
 def policy_linear(rel_delta: float, eta: float, lo_ppm: int, hi_ppm: int) -> int:
     return int(lib().oracle_policy_linear(rel_delta, eta, lo_ppm, hi_ppm))
+
+
+def clr_trace(p_low_ppm: int, p_high_ppm: int, iters_per_epoch: int, critical) -> np.ndarray:
+    """Threshold in force after each step of the epoch-level controller."""
+    crit = np.ascontiguousarray(critical, dtype=np.uint8)
+    out = np.empty(crit.size, dtype=np.uint32)
+    lib().oracle_clr_trace(p_low_ppm, p_high_ppm, iters_per_epoch, _p(crit), crit.size, _p(out))
+    return out

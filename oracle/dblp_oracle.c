@@ -282,3 +282,23 @@ uint32_t oracle_policy_linear(double rel_delta, double eta, uint32_t lo_ppm, uin
     if (!(x < 1.0)) x = 1.0;
     return quantise_1000((double)hi_ppm - ((double)hi_ppm - (double)lo_ppm) * x);
 }
+
+/*
+ * Epoch-level controller (Alg. Server, the tolerance block; Sec. "Centralized All-Reduce
+ * Architecture").  Written as the paper's loop reads: the threshold is initialised to P_low;
+ * for each step, if the step is the beginning of an epoch the threshold is reset to P_high and
+ * then, if CLR is detected, set to P_low.  `critical[s]` is the Eq. 1 outcome of step s;
+ * bound_after[s] receives the threshold in force once step s has been handled.
+ */
+void oracle_clr_trace(uint32_t p_low_ppm, uint32_t p_high_ppm, uint32_t iters_per_epoch,
+                      const uint8_t* critical, uint64_t n_steps, uint32_t* bound_after) {
+    uint32_t threshold = p_low_ppm;
+    for (uint64_t step = 0; step < n_steps; ++step) {
+        int at_epoch_start = (step % iters_per_epoch) == 0;
+        if (at_epoch_start) {
+            threshold = p_high_ppm;
+            if (critical[step]) threshold = p_low_ppm;
+        }
+        bound_after[step] = threshold;
+    }
+}

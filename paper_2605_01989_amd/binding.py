@@ -22,7 +22,7 @@ K_INDEX, K_GATHER, K_PROBE, K_FINALIZE = 0, 1, 2, 3
 EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_begin_round", "dblp_packetize",
            "dblp_apply_arrivals", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
            "dblp_get_bitmap", "dblp_get_counters", "dblp_set_prev_norm", "dblp_get_prev_norm",
-           "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear"]
+           "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear", "dblp_clr_init", "dblp_clr_step"]
 
 
 class DblpError(RuntimeError):
@@ -33,6 +33,13 @@ class DblpError(RuntimeError):
 
 class _Bucket(ctypes.Structure):
     _fields_ = [("elem_offset", ctypes.c_uint64), ("elem_count", ctypes.c_uint64)]
+
+
+class ClrState(ctypes.Structure):
+    """dblp_clr_state: the caller-owned state of the epoch-level tolerance controller."""
+    _fields_ = [("p_low_ppm", ctypes.c_uint32), ("p_high_ppm", ctypes.c_uint32),
+                ("iters_per_epoch", ctypes.c_uint32), ("bound_ppm", ctypes.c_uint32),
+                ("step", ctypes.c_uint64)]
 
 
 class _Config(ctypes.Structure):
@@ -73,6 +80,9 @@ def lib():
         L.dblp_last_error.restype = ctypes.c_char_p
         for name in ("dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear"):
             getattr(L, name).restype = u32
+        L.dblp_clr_init.argtypes = [ctypes.POINTER(ClrState), u32, u32, u32]
+        L.dblp_clr_step.argtypes = [ctypes.POINTER(ClrState), i32]
+        L.dblp_clr_step.restype = u32
         L.dblp_policy_two_level.argtypes = [i32, u32, u32]
         L.dblp_policy_three_level.argtypes = [dbl, dbl, u32, u32, u32]
         L.dblp_policy_linear.argtypes = [dbl, dbl, u32, u32]
@@ -90,6 +100,23 @@ def policy_three_level(rel_delta: float, eta: float, tight_ppm: int, mid_ppm: in
 
 def policy_linear(rel_delta: float, eta: float, lo_ppm: int, hi_ppm: int) -> int:
     return int(lib().dblp_policy_linear(rel_delta, eta, lo_ppm, hi_ppm))
+
+
+class ClrController:
+    """Epoch-level tolerance controller (dblp_clr_init / dblp_clr_step)."""
+
+    def __init__(self, p_low_ppm: int, p_high_ppm: int, iters_per_epoch: int):
+        self.state = ClrState()
+        rc = lib().dblp_clr_init(ctypes.byref(self.state), p_low_ppm, p_high_ppm, iters_per_epoch)
+        if rc != OK:
+            raise DblpError(rc, "dblp_clr_init: bad arguments")
+
+    @property
+    def bound_ppm(self) -> int:
+        return int(self.state.bound_ppm)
+
+    def step(self, critical: bool) -> int:
+        return int(lib().dblp_clr_step(ctypes.byref(self.state), int(critical)))
 
 
 def _ptr(t):

@@ -1274,3 +1274,18 @@ extern "C" uint32_t dblp_policy_linear(double rel_delta, double eta, uint32_t lo
     const double ppm = (double)hi_ppm - ((double)hi_ppm - (double)lo_ppm) * x;
     return (uint32_t)(floor(ppm / 1000.0 + 0.5)) * 1000u;
 }
+
+extern "C" int dblp_clr_init(dblp_clr_state* st, uint32_t p_low_ppm, uint32_t p_high_ppm, uint32_t iters_per_epoch) {
+    if (!st || iters_per_epoch == 0 || p_low_ppm > 1000000u || p_high_ppm > 1000000u) return DBLP_EINVAL;
+    st->p_low_ppm = p_low_ppm; st->p_high_ppm = p_high_ppm; st->iters_per_epoch = iters_per_epoch;
+    st->bound_ppm = p_low_ppm;      // training starts in the critical regime
+    st->step = 0;
+    return DBLP_OK;
+}
+
+extern "C" uint32_t dblp_clr_step(dblp_clr_state* st, int critical) {
+    if (st->step % st->iters_per_epoch == 0)      // first iteration of an epoch: re-decide
+        st->bound_ppm = critical ? st->p_low_ppm : st->p_high_ppm;
+    st->step += 1;
+    return st->bound_ppm;
+}

@@ -13,7 +13,6 @@ import numpy as np
 
 import workloads as wl
 
-MAX_DRAWN_ROUNDS = 6   # retransmission rounds with a drawn loss pattern; later rounds lose nothing
 
 
 @dataclass
@@ -46,7 +45,7 @@ class Scenario:
     def survive(self, rnd: int) -> np.ndarray:
         if rnd == 0:
             return self.survive0
-        if rnd > MAX_DRAWN_ROUNDS:
+        if rnd > self.w.drawn_rounds:
             return np.ones_like(self.survive0)
         if rnd not in self._survive_cache:
             self._survive_cache[rnd] = self.w.survive(self.it, rnd, self.slot_of)
@@ -122,7 +121,7 @@ class OracleRx:
         return self.o.counters()
 
 
-def run_iteration(rx, sc: Scenario, bound_ppm: int, max_rounds: int = 64) -> dict:
+def run_iteration(rx, sc: Scenario, bound_ppm: int, max_rounds: int = 256) -> dict:
     """One full iteration on receiver `rx`.  Returns everything observable."""
     L = sc.L
     rx.begin_round(sc.rnd_id)

@@ -55,3 +55,16 @@ def test_null_context_calls_return_einval_without_a_gpu():
     assert L.dblp_begin_round(None, 1) == binding.EINVAL
     assert L.dblp_destroy(None) == binding.OK
     assert L.dblp_layout(None, None, None, None) == binding.EINVAL
+
+
+def test_epoch_controller_matches_oracle_trace_and_starts_low():
+    import numpy as np
+    rng = np.random.default_rng(4)
+    for ipe in (1, 3, 93):
+        crit = (rng.random(400) < 0.3).astype(np.uint8)
+        ctl = dblp.ClrController(8000, 408000, ipe)
+        assert ctl.bound_ppm == 8000                       # the threshold is initialised to P_low
+        got = [ctl.step(bool(c)) for c in crit]
+        assert got == oracle.clr_trace(8000, 408000, ipe, crit).tolist()
+    with pytest.raises(dblp.DblpError):
+        dblp.ClrController(8000, 408000, 0)

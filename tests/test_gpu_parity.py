@@ -338,3 +338,33 @@ def test_cfg5_chunked_scaled_down():
     stats, got, ref = run_both(sc, 20_000)
     assert ref["rounds"] >= 1
     print("cfg5s", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+
+
+def test_paper_burst_workload_with_epoch_controller():
+    """The paper's own shape (3 workers, one accounting unit per worker, Table 1 tolerances) on a
+    small gradient: 3 epochs of 3 iterations, a 70 % whole-iteration burst in a non-critical epoch.
+    GPU and oracle run the retransmission loop under the epoch-level controller of Alg. Server."""
+    import oracle as orc
+    import paper_2605_01989_amd as dblp
+    w = wl.scaled_down(wl.paper_model_workload("effnetb0", 0.7, burst_iters=(7,), iterations=9), 200_000)
+    w = dataclasses.replace(w, scale_schedule=(1, 1, 1, 0.4, 0.4, 0.4, 0.4, 0.4, 0.4))
+    lo, hi = w.policy["low_ppm"], w.policy["high_ppm"]
+    assert (lo, hi) == (8000, 408000) and w.layout.B == 1 and w.layout.W == 3
+    ctl = dblp.ClrController(lo, hi, 3)
+    bound, crit, prev_o, prev_g, rounds, bounds = lo, [], None, None, [], []
+    for it in range(9):
+        sc = build_scenario(w, it)
+        o, g = both(sc)
+        o.o.set_prev_norm(prev_o)
+        g.agg.set_prev_norm(prev_g)
+        ref = run_iteration(o, sc, bound)
+        got = run_iteration(g, sc, bound)
+        compare_results(got, ref, sc)
+        prev_o, prev_g = ref["norm"], got["norm"]
+        rounds.append(ref["rounds"]); bounds.append(bound)
+        crit.append(ref["critical"])
+        bound = ctl.step(got["critical"])
+        assert bound == int(orc.clr_trace(lo, hi, 3, crit)[-1])
+    assert bounds == [lo, lo, lo, lo, lo, lo, lo, hi, hi]     # epoch 0 and 1 critical, epoch 2 not
+    assert rounds[7] == 2          # missing after the first transmission 0.7, then 0.49, then 0.343 <= 0.408
+    assert max(rounds[:7]) <= 2

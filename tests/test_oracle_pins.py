@@ -355,3 +355,14 @@ def test_create_rejects_bad_tables():
         oracle.Oracle(2, 10, 4, [0, 5], [5, 4])      # does not reach N
     with pytest.raises(ValueError):
         oracle.Oracle(0, 10, 4, [0], [10])
+
+
+def test_epoch_controller_follows_the_server_algorithm():
+    """Alg. Server: threshold starts at P_low; only the first step of an epoch re-decides: reset to
+    P_high, back to P_low if that step is critical.  Hand-traced sequence, 3 steps per epoch."""
+    lo, hi = 8000, 408000
+    crit = [1, 0, 0,   0, 1, 1,   1, 0, 0,   0, 0, 0]
+    want = [lo, lo, lo, hi, hi, hi, lo, lo, lo, hi, hi, hi]
+    assert oracle.clr_trace(lo, hi, 3, crit).tolist() == want
+    # one step per epoch degenerates to the per-iteration two-level rule
+    assert oracle.clr_trace(lo, hi, 1, [1, 0, 1, 0]).tolist() == [lo, hi, lo, hi]

@@ -348,6 +348,7 @@ class Workload:
     chunk_buckets: int = 0   # >0: packets are applied in steps of this many buckets
     seed: int = MASTER_SEED
     scale_schedule: tuple = ()  # per-iteration multiplier on sigma (empty: all 1)
+    drawn_rounds: int = 6       # retransmission rounds that draw loss; later rounds lose nothing
 
     def sigma_at(self, it: int) -> float:
         return self.sigma * (self.scale_schedule[it] if self.scale_schedule else 1.0)
@@ -361,6 +362,11 @@ class Workload:
         if k["kind"] == "ge":
             return survive_gilbert_elliott(self.seed, it, rnd, L.W, L.n_pkts, k["p_good"], k["p_bad"],
                                            k["p_g2b"], k["p_b2g"])
+        if k["kind"] == "burst_iter":
+            # the paper's microburst: a whole iteration (first transmission and every
+            # retransmission round of it) suffers loss rate p_burst; other iterations p_bg
+            p = k["p_burst"] if it in k["burst_iters"] else k["p_bg"]
+            return survive_bernoulli(self.seed, it, rnd, L.W, L.n_pkts, p)
         if k["kind"] == "microburst":
             if rnd > 0:  # retransmissions see only the background loss
                 return survive_bernoulli(self.seed, it, rnd, L.W, L.n_pkts, k["p_iid"])
@@ -420,6 +426,22 @@ def workload(name: str, seed: int = MASTER_SEED) -> Workload:
                         iterations=20, tail_ppm=10000, tail_mul=100.0, chunk_buckets=44,
                         scale_schedule=_decay_schedule(20), seed=seed)
     raise ValueError(name)
+
+
+def paper_model_workload(name: str, burst_rate: float, burst_iters, iterations: int, seed: int = MASTER_SEED,
+                         p_bg: float = 0.002) -> Workload:
+    """The paper's own setting, as far as it is stated: 3 workers and one server, one accounting
+    unit per worker and round (a single bucket), MTU-filling packets, parameter counts of Table 1.
+    Whole-iteration microbursts at `burst_iters` with loss rate `burst_rate` (60-90 % in the paper);
+    the background loss p_bg is this repository's choice (the paper's network is a black box)."""
+    n_params = {"effnetb0": 5_288_548, "resnet50": 25_557_032, "alexnet": 61_100_840, "gpt2s": 124_439_808}[name]
+    off, cnt = buckets_from_sizes([n_params])
+    p_low = 24_000 if name == "resnet50" else 8_000
+    return Workload(f"paper_{name}", Layout(3, n_params, 366, off, cnt), 1e-3,
+                    dict(kind="burst_iter", p_bg=p_bg, p_burst=burst_rate, burst_iters=tuple(burst_iters)),
+                    "interleave", "shuffle",
+                    dict(kind="two_level", low_ppm=p_low, high_ppm=p_low + 400_000, eta=0.5),
+                    iterations=iterations, seed=seed, drawn_rounds=1_000_000)
 
 
 def scaled_down(wl: Workload, N: int, name: str | None = None) -> Workload:
