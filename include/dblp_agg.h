@@ -108,6 +108,16 @@ int dblp_packetize(dblp_ctx* ctx, uint32_t w, uint16_t round, const float* d_gra
                    const uint32_t* d_slot_map, uint64_t slot_base, uint64_t n_slots,
                    void* d_packets, uint16_t* d_src_worker);
 
+/* Sender side, retransmission (Alg. "DBLP Send": after a bitmap reply only the lost packets
+ * are sent again).  Entry i of d_retx_list, (w << 32) | seq as produced by dblp_loss_account,
+ * becomes the packet at slot slot_base + i of d_packets (and d_src_worker[slot_base + i] = w).
+ * h_grads: HOST array of n_workers DEVICE pointers, h_grads[w] = worker w's whole gradient
+ * (N floats).  n_slots is the capacity of d_packets / d_src_worker.  An entry whose worker or
+ * seq is out of range is skipped and the call returns EINVAL.  Synchronises the stream. */
+int dblp_packetize_list(dblp_ctx* ctx, uint16_t round, const float* const* h_grads,
+                        const uint64_t* d_retx_list, uint64_t n_entries, uint64_t slot_base,
+                        uint64_t n_slots, void* d_packets, uint16_t* d_src_worker);
+
 /* Alg. "DBLP_RECV", chunk-arrival branch, for one batch of arrivals (property 1 of the
  * paper: packets are applied as they arrive, in any order).
  *   d_packets     n_slots wire packets, 16-byte aligned, `stride` bytes apart

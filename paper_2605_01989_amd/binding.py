@@ -19,7 +19,7 @@ _NAMES = {EINVAL: "DBLP_EINVAL", ENOMEM: "DBLP_ENOMEM", ECAPACITY: "DBLP_ECAPACI
 COMP_ZEROFILL_MEAN = 0
 K_INDEX, K_GATHER, K_PROBE, K_FINALIZE = 0, 1, 2, 3
 
-EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_begin_round", "dblp_packetize",
+EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_begin_round", "dblp_packetize", "dblp_packetize_list",
            "dblp_apply_arrivals", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
            "dblp_get_bitmap", "dblp_get_counters", "dblp_set_prev_norm", "dblp_get_prev_norm",
            "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear", "dblp_clr_init", "dblp_clr_step"]
@@ -66,6 +66,7 @@ def lib():
         L.dblp_layout.argtypes = [vp, ctypes.POINTER(u64), ctypes.POINTER(u32), ctypes.POINTER(u64)]
         L.dblp_begin_round.argtypes = [vp, u16]
         L.dblp_packetize.argtypes = [vp, u32, u16, vp, u64, u64, u64, u64, vp, u64, u64, vp, vp]
+        L.dblp_packetize_list.argtypes = [vp, u16, ctypes.POINTER(vp), vp, u64, u64, u64, vp, vp]
         L.dblp_apply_arrivals.argtypes = [vp, vp, vp, u64, vp, vp, u64]
         L.dblp_loss_account.argtypes = [vp, u32, vp, vp, u64, ctypes.POINTER(u64), ctypes.POINTER(i32)]
         L.dblp_finalize.argtypes = [vp, i32, vp]
@@ -171,6 +172,14 @@ class Aggregator:
         self._check(lib().dblp_packetize(self._h, w, rnd & 0xFFFF, _ptr(d_grad), elem_base, d_grad.numel(),
                                          first_seq, n_pkts, _ptr(d_slot_map), slot_base, n_slots,
                                          _ptr(d_packets), _ptr(d_src_worker)))
+
+    def packetize_list(self, rnd, d_grads, d_retx_list, n_entries, d_packets, d_src_worker, slot_base=0, n_slots=None):
+        """d_grads: one device tensor per worker (whole gradient)."""
+        if n_slots is None:
+            n_slots = d_src_worker.numel()
+        ptrs = (ctypes.c_void_p * self.W)(*[t.data_ptr() for t in d_grads])
+        self._check(lib().dblp_packetize_list(self._h, rnd & 0xFFFF, ptrs, _ptr(d_retx_list), n_entries, slot_base,
+                                              n_slots, _ptr(d_packets), _ptr(d_src_worker)))
 
     def apply_arrivals(self, d_packets, d_src_worker, n_slots, d_mask_words=None, d_order=None, n_arrivals=None):
         if n_arrivals is None:

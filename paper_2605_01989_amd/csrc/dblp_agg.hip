@@ -180,6 +180,42 @@ __global__ __launch_bounds__(256) void packetize_kernel(Geo g, u32 w, u32 round,
     }
 }
 
+struct GradPtrs { const float* p[DBLP_MAX_WORKERS]; };
+
+// One wave per list entry (w << 32 | seq): worker w's packet seq -> slot slot_base + i.
+__global__ __launch_bounds__(256) void packetize_list_kernel(Geo g, GradPtrs grads, u32 round, const u64* __restrict__ list,
+                                                             u64 n, u64 slot_base, uint8_t* __restrict__ packets,
+                                                             uint16_t* __restrict__ src_worker, u64* __restrict__ counters) {
+    const u32 lane = lane_id();
+    const u64 wave = ((u64)blockIdx.x * blockDim.x + threadIdx.x) / WAVE;
+    const u64 n_waves = (u64)gridDim.x * blockDim.x / WAVE;
+    for (u64 i = wave; i < n; i += n_waves) {
+        const u64 e = list[i];
+        const u32 w = (u32)(e >> 32), seq = (u32)e;
+        if (w >= g.W || seq >= g.n_pkts) {
+            if (lane == 0) atomicAdd(&counters[C_PKT_BAD], 1ull);
+            continue;
+        }
+        const u32 b = find_bucket(g.first_seq, g.B, seq);
+        u64 elem; u32 len;
+        packet_span(g, seq, b, &elem, &len);
+        const float* src = grads.p[w] + elem;
+        uint4* dst = (uint4*)(packets + (slot_base + i) * g.stride);
+        for (u32 u = lane; u < g.units; u += WAVE) {
+            u32 q[4];
+            #pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const u32 i4 = 4 * u + c;
+                if (i4 == 0) q[c] = seq;
+                else if (i4 == 1) q[c] = (round & 0xFFFFu) | (len << 16);
+                else q[c] = (i4 - 2 < len) ? __float_as_uint(src[i4 - 2]) : 0u;
+            }
+            dst[u] = make_uint4(q[0], q[1], q[2], q[3]);
+        }
+        if (lane == 0) src_worker[slot_base + i] = (uint16_t)w;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // receiver step 1: index the arrivals
 // ------------------------------------------------------------------------------------------
@@ -1066,6 +1102,34 @@ extern "C" int dblp_packetize(dblp_ctx* c, uint32_t w, uint16_t round, const flo
             HIP_TRY(c, hipMemsetAsync(c->d_counters + C_PKT_BAD, 0, sizeof(u64), c->stream));
             return fail(c, DBLP_EINVAL, "packetize: slot map entry outside the packet buffer");
         }
+    }
+    return DBLP_OK;
+}
+
+extern "C" int dblp_packetize_list(dblp_ctx* c, uint16_t round, const float* const* h_grads, const uint64_t* d_list,
+                                   uint64_t n, uint64_t slot_base, uint64_t n_slots, void* d_packets,
+                                   uint16_t* d_src_worker) {
+    if (!c) return DBLP_EINVAL;
+    if (n == 0) return DBLP_OK;
+    if (!h_grads || !d_list || !d_packets || !d_src_worker) return fail(c, DBLP_EINVAL, "packetize_list: null pointer");
+    if (((uintptr_t)d_packets & 15) != 0) return fail(c, DBLP_EINVAL, "packetize_list: d_packets must be 16-byte aligned");
+    if (slot_base > n_slots || n > n_slots - slot_base) return fail(c, DBLP_EINVAL, "packetize_list: slots exceed buffer");
+    GradPtrs gp;
+    for (u32 w = 0; w < DBLP_MAX_WORKERS; ++w) gp.p[w] = nullptr;
+    for (u32 w = 0; w < c->g.W; ++w) {
+        if (!h_grads[w]) return fail(c, DBLP_EINVAL, "packetize_list: null gradient pointer");
+        gp.p[w] = h_grads[w];
+    }
+    HIP_TRY(c, hipSetDevice(c->device));
+    hipLaunchKernelGGL(packetize_list_kernel, dim3(grid_for(c, (n + 3) / 4, 16)), dim3(256), 0, c->stream, c->g, gp,
+                       (u32)round, (const u64*)d_list, (u64)n, (u64)slot_base, (uint8_t*)d_packets, d_src_worker,
+                       c->d_counters);
+    LAUNCH_CHECK(c, "packetize_list");
+    HIP_TRY(c, hipMemcpyAsync(c->h_mailbox + 4, c->d_counters + C_PKT_BAD, sizeof(u64), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    if (c->h_mailbox[4]) {
+        HIP_TRY(c, hipMemsetAsync(c->d_counters + C_PKT_BAD, 0, sizeof(u64), c->stream));
+        return fail(c, DBLP_EINVAL, "packetize_list: list entry with worker or seq out of range");
     }
     return DBLP_OK;
 }

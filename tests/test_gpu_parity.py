@@ -368,3 +368,82 @@ def test_paper_burst_workload_with_epoch_controller():
     assert bounds == [lo, lo, lo, lo, lo, lo, lo, hi, hi]     # epoch 0 and 1 critical, epoch 2 not
     assert rounds[7] == 2          # missing after the first transmission 0.7, then 0.49, then 0.343 <= 0.408
     assert max(rounds[:7]) <= 2
+
+
+# ------------------------------------------------------------------------------ sender side / broadcast leg
+def test_packetize_list_rebuilds_exactly_the_listed_packets():
+    """Alg. DBLP Send: only the lost packets are sent again.  The list-driven packetiser must emit
+    byte-for-byte the packets the oracle's packetiser makes for the same (worker, seq) entries, and
+    applying them must complete the round exactly like re-delivering the original slots."""
+    import torch
+    sc = build_scenario(mk(5, [366 * 120 + 9, 700, 3], 366, 0.15, place="shuffle", order="shuffle"))
+    L = sc.L
+    o, g = both(sc)
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        b = sc.batches[0]
+        rx.apply(b.slot_base, b.n_slots, b.mask, b.order)
+    mo, lo, co, _ = o.loss_account(0)
+    mg, lg, cg, _ = g.loss_account(0)
+    assert np.array_equal(lo, lg) and co == cg > 0
+    d_grads = [torch.from_numpy(sc.grad(w)).cuda() for w in range(L.W)]
+    d_pk = torch.zeros(cg * L.stride, dtype=torch.uint8, device="cuda")
+    d_src = torch.zeros(cg, dtype=torch.int16, device="cuda")
+    g.agg.packetize_list(sc.rnd_id, d_grads, g.d_list, cg, d_pk, d_src)
+    ref_pk = np.zeros(co * L.stride, dtype=np.uint8)
+    ref_src = np.zeros(co, dtype=np.uint16)
+    for i, e in enumerate(lo.tolist()):
+        o.o.packetize(e >> 32, sc.rnd_id, sc.grad(e >> 32), 0, e & 0xFFFFFFFF, 1, ref_pk, ref_src, slot_base=i)
+    assert np.array_equal(d_pk.cpu().numpy(), ref_pk)
+    assert np.array_equal(d_src.cpu().numpy().view(np.uint16), ref_src)
+    g.agg.apply_arrivals(d_pk, d_src, cg)                      # resend everything, nothing lost
+    o.o.apply_arrivals(ref_pk, ref_src, co)
+    assert g.loss_account(0)[3] and o.loss_account(0)[3]
+    assert g.counters() == o.counters()
+    full = np.ones((L.W, L.n_pkts), np.uint8)
+    assert np.array_equal(g.bitmap(), full)
+    from harness import abs_scale
+    ref = o.finalize()
+    assert np.allclose(ref, definition_mean(sc, full), rtol=1e-14, atol=0)
+    assert (np.abs(g.finalize().astype(np.float64) - ref) / abs_scale(sc, full)).max() <= FLOAT_TOL
+    bad = torch.tensor([(7 << 32) | 1], dtype=torch.int64, device="cuda")     # worker 7 of 5
+    from paper_2605_01989_amd import DblpError
+    with pytest.raises(DblpError):
+        g.agg.packetize_list(sc.rnd_id, d_grads, bad, 1, d_pk, d_src)
+
+
+def test_broadcast_leg_each_receiver_reconstructs_with_zero_fill():
+    """Alg. Server, last statement, and Alg. Worker: the mean is sent back with DBLP_SEND; every worker
+    is an independent receiver (no sum): what it lost stays zero.  One single-sender context per
+    receiver; the sender's packets are built once from the aggregated gradient."""
+    import torch
+    import oracle as orc
+    import paper_2605_01989_amd as dblp
+    sc = build_scenario(mk(3, [366 * 50 + 17, 901], 366, 0.0))
+    L = sc.L
+    o, g = both(sc)
+    ref = run_iteration(o, sc, 0)
+    got = run_iteration(g, sc, 0)
+    mean = g.d_out                                            # device tensor, the server's result
+    bc = dblp.Aggregator(1, L.N, L.P, L.bucket_off, L.bucket_cnt)
+    pk = torch.zeros(L.n_pkts * L.stride, dtype=torch.uint8, device="cuda")
+    src = torch.zeros(L.n_pkts, dtype=torch.int16, device="cuda")
+    bc.packetize(0, 9, mean, 0, 0, L.n_pkts, pk, src)
+    oc = orc.Oracle(1, L.N, L.P, L.bucket_off, L.bucket_cnt)
+    opk = np.zeros(L.n_pkts * L.stride, dtype=np.uint8)
+    osrc = np.zeros(L.n_pkts, dtype=np.uint16)
+    oc.packetize(0, 9, got["out"], 0, 0, L.n_pkts, opk, osrc)
+    assert np.array_equal(pk.cpu().numpy(), opk)
+    out = torch.empty(L.N, dtype=torch.float32, device="cuda")
+    for r in range(3):                                        # three receivers, three loss patterns
+        surv = wl.survive_bernoulli(sc.w.seed, 0, 10 + r, 1, L.n_pkts, 0.2)
+        words = np.packbits(np.pad(surv[0], (0, (-L.n_pkts) % 64)), bitorder="little").view(np.uint64)
+        bc.begin_round(9)
+        bc.apply_arrivals(pk, src, L.n_pkts, torch.from_numpy(words.view(np.int64)).cuda())
+        bc.finalize(out)
+        oc.begin_round(9)
+        oc.apply_arrivals(opk, osrc, L.n_pkts, words)
+        want = oc.finalize()
+        assert np.array_equal(out.cpu().numpy().astype(np.float64), want)     # one sender: exact
+        pkt_of = np.concatenate([int(L.first_seq[b]) + np.arange(int(L.bucket_cnt[b])) // L.P for b in range(L.B)])
+        assert np.all(want[surv[0, pkt_of] == 0] == 0.0) and np.any(want != 0)
