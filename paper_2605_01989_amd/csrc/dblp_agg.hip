@@ -427,7 +427,7 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
 // Staged variant of the gather (used whenever two groups of packets fit in LDS).
 // Mixing the accumulator stores into the waves that stream the payloads costs far more than the
 // stores' bytes (a payload-only loop sustains 6.2 TB/s on this chip, the same loop with its
-// 3 % of stores 4.9 TB/s).  Here GS_READERS waves only load and add, and hand each summed
+// 3 % of stores 4.9 TB/s).  Here up to GS_READERS waves only load and add, and hand each summed
 // packet to LDS; one extra writer wave drains the previous group from LDS to the accumulator
 // while the readers work on the next one (double-buffered).  Because the writer reads LDS at
 // arbitrary float offsets, its global accesses are 16-byte aligned float4s whatever the
@@ -435,10 +435,10 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
 #ifndef GS_READERS
 #define GS_READERS 8
 #endif
-#ifndef GS_BLOCKS_PER_CU
-#define GS_BLOCKS_PER_CU 3
-#endif
 #define GS_LDS_BUDGET (48u * 1024u)   // bytes for the two packet buffers
+#ifndef GS_MAX_PER_CU
+#define GS_MAX_PER_CU 2               // blocks per CU: measured best for 1.5 KB and 4 KB packets (more waves
+#endif                                // in flight only spread the DRAM accesses over more open rows)
 
 // Sum of one whole packet over the workers in `sub`: lane l holds 16-byte units l, l+64, ...
 // (NP of them).  All NP loads of one worker's packet are issued together, so a packet's
@@ -489,6 +489,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
     if (batch_is_sparse(counters, g.W)) return;     // left to the direct kernel
     const u32 lane = lane_id();
     const u32 wave = threadIdx.x / WAVE;
+    const u32 n_readers = blockDim.x / WAVE - 1;      // the last wave of the block is the writer
     const u32 W = g.W;
     const u32 upp = g.stride >> 4;                  // float4 units per packet
     float4* buf0 = sh_dyn;
@@ -505,13 +506,13 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
     for (u32 it = 0; it <= n_it; ++it) {            // one extra turn so the writer drains the last group
         const u32 cur = it & 1;
         const u32 seq0 = (grp0 + it * gridDim.x) << sub_log2;
-        if (wave < GS_READERS) {
+        if (wave < n_readers) {
             if (it < n_it) {
                 // ---- phase A: arrival index -> bitmap bits, slots, spans
                 const u32 seq_l = seq0 + s_lane;
                 const u32 word = seq0 >> 6, shift = seq0 & 63;
                 u32 new_or = 0, old_or = 0;
-                for (u32 w0 = wave * wpl; w0 < W; w0 += GS_READERS * wpl) {
+                for (u32 w0 = wave * wpl; w0 < W; w0 += n_readers * wpl) {
                     const u32 w = w0 + w_sub;
                     const bool valid = w < W && seq_l < g.n_pkts;
                     u64 p = NONE64, bits = 0;
@@ -534,7 +535,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                     }
                     accepted += (u32)__popcll(nb);
                 }
-                if (wave == GS_READERS - 1 && lane < sub && seq_l < g.n_pkts) {
+                if (wave == n_readers - 1 && lane < sub && seq_l < g.n_pkts) {
                     const u32 b = find_bucket(g.first_seq, g.B, seq_l);
                     u64 elem; u32 len;
                     packet_span(g, seq_l, b, &elem, &len);
@@ -571,15 +572,14 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
             }
         }
         __syncthreads();
-        if (wave < GS_READERS && it < n_it) {
+        if (wave < n_readers && it < n_it) {
             // ---- phase B: payload gather, worker order, results to LDS
             u32 new_any = 0, old_any = 0;
-            #pragma unroll
-            for (int i = 0; i < GS_READERS; ++i) { new_any |= sh_new[i]; old_any |= sh_old[i]; }
+            for (u32 i = 0; i < n_readers; ++i) { new_any |= sh_new[i]; old_any |= sh_old[i]; }
             if (threadIdx.x == 0) sh_flag_new[cur] = new_any;
             float4* dstbuf = cur ? buf1 : buf0;
             if (NP > 0) {
-                for (u32 t = wave; t < sub; t += GS_READERS) {
+                for (u32 t = wave; t < sub; t += n_readers) {
                     if (!((new_any >> t) & 1u)) continue;
                     const u32 len = sh_len[cur][t];
                     const u32 units = (len + 2 + 3) >> 2;        // 16-byte units holding header + payload
@@ -608,7 +608,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                 }
             } else {
             const u32 items = n_pass << sub_log2;
-            for (u32 i = wave; i < items; i += GS_READERS) {
+            for (u32 i = wave; i < items; i += n_readers) {
                 const u32 t = i & (sub - 1), pass = i >> sub_log2;
                 if (!((new_any >> t) & 1u)) continue;
                 const u32 len = sh_len[cur][t];
@@ -636,7 +636,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
         }
         __syncthreads();
     }
-    if (wave < GS_READERS && lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
+    if (wave < n_readers && lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1161,11 +1161,16 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
             const size_t lds = 2ull * sub * g.stride + (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
             const u64 groups = ((u64)g.n_pkts + sub - 1) / sub;
             const u32 n_pass = (g.units + WAVE - 1) / WAVE;
+            const u32 readers = sub < GS_READERS ? sub : GS_READERS;   // a reader wave takes whole packets
+            u32 per_cu = (u32)((160u * 1024u) / (lds + 1024));
+            if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
+            if (per_cu > GS_MAX_PER_CU) per_cu = GS_MAX_PER_CU;
+            if (per_cu < 1) per_cu = 1;
             void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, u64*, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
-            hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, GS_BLOCKS_PER_CU)), dim3((GS_READERS + 1) * WAVE),
+            hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, per_cu)), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
                                c->d_counters, sub, sub_log2, n_pass);
         }
