@@ -447,3 +447,32 @@ def test_broadcast_leg_each_receiver_reconstructs_with_zero_fill():
         assert np.array_equal(out.cpu().numpy().astype(np.float64), want)     # one sender: exact
         pkt_of = np.concatenate([int(L.first_seq[b]) + np.arange(int(L.bucket_cnt[b])) // L.P for b in range(L.B)])
         assert np.all(want[surv[0, pkt_of] == 0] == 0.0) and np.any(want != 0)
+
+
+# ------------------------------------------------------------------------------ randomized sweep
+@pytest.mark.parametrize("seed", range(32))
+def test_random_geometry_sweep(seed):
+    """Seeded random worker counts, packet lengths, bucket tables, loss rates, placements, orders
+    and bounds; two iterations each so the stored previous norm is exercised."""
+    rng = np.random.default_rng(1000 + seed)
+    W = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16, 17, 31, 32, 33, 48, 64]))
+    P = int(rng.choice([1, 2, 5, 16, 61, 62, 63, 64, 100, 254, 255, 256, 257, 366, 510, 511, 1024, 1500, 2900]))
+    n_b = int(rng.integers(1, 9))
+    sizes = [int(x) for x in np.maximum(1, (rng.lognormal(0, 1.5, n_b) * P * rng.integers(1, 40)).astype(np.int64))]
+    while sum(sizes) * W > 6_000_000:
+        sizes = [max(1, s // 2) for s in sizes]
+    loss = float(rng.choice([0.0, 0.01, 0.1, 0.5, 0.95]))
+    ppm = int(rng.choice([0, 8_000, 50_000, 408_000, 1_000_000]))
+    place = str(rng.choice(["worker_major", "interleave", "shuffle"]))
+    order = str(rng.choice(["identity", "reverse", "shuffle"]))
+    w = mk(W, sizes, P, loss, seed=seed, place=place, order=order)
+    prev_o = prev_g = None
+    for it in range(2):
+        sc = build_scenario(w, it)
+        o, g = both(sc)
+        o.o.set_prev_norm(prev_o)
+        g.agg.set_prev_norm(prev_g)
+        ref = run_iteration(o, sc, ppm)
+        got = run_iteration(g, sc, ppm)
+        compare_results(got, ref, sc)
+        prev_o, prev_g = ref["norm"], got["norm"]
