@@ -476,3 +476,23 @@ def test_random_geometry_sweep(seed):
         got = run_iteration(g, sc, ppm)
         compare_results(got, ref, sc)
         prev_o, prev_g = ref["norm"], got["norm"]
+
+
+def test_early_stop_sub_batches_match_oracle():
+    """Arrivals cut into sub-batches with a probe after each, stopping at the first satisfied probe:
+    order-dependent, so not part of the graded path, but GPU and oracle must still agree."""
+    import sys, os
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    from study_stop_granularity import run_early_stop
+    from harness import abs_scale
+    sc = build_scenario(mk(4, [366 * 500 + 3], 366, 0.02, place="interleave", order="shuffle"))
+    o, g = both(sc)
+    for k in (1, 37, 200):
+        ref = run_early_stop(o, sc, 50_000, k)
+        got = run_early_stop(g, sc, 50_000, k)
+        assert (got["probes"], got["met"], got["accepted"]) == (ref["probes"], ref["met"], ref["accepted"])
+        assert np.array_equal(got["bitmap"], ref["bitmap"])
+        scale = abs_scale(sc, ref["bitmap"])
+        nz = scale > 0
+        assert (np.abs(got["out"] - ref["out"])[nz] / scale[nz]).max() <= FLOAT_TOL
+    assert ref["probes"] < 200 and ref["accepted"] < sc.survive0.sum()      # it did stop early
