@@ -7,8 +7,8 @@ the result independent of the arrival permutation.  Here the arrivals of one rou
 K equal sub-batches in arrival order, the threshold is tested after each, and the round stops at
 the first probe that is satisfied: the remaining arrivals are never applied ("early stop").
 K = 1 is the graded behaviour; large K approaches the paper's per-chunk test.  The outcome then
-depends on the arrival order, which is why this lives outside the parity-graded path; the GPU
-result is still checked against the oracle driven through the same sub-batches.
+depends on the arrival order, which is why this lives outside the parity-graded path (a GPU test
+drives the CPU checker through the same sub-batches).
 
 Prints one JSON object.  GPU required.
 """
@@ -62,7 +62,7 @@ def main():
                     help="keep the per-layer buckets (default: one accounting unit per worker, the paper's)")
     args = ap.parse_args()
     import workloads as wl
-    from harness import GpuRx, OracleRx, abs_scale, build_scenario, FLOAT_TOL
+    from harness import GpuRx, build_scenario
     w = wl.workload("cfg2")
     if args.elems != w.layout.N:
         w = wl.scaled_down(w, args.elems)
@@ -71,17 +71,11 @@ def main():
         L = w.layout
         w = dataclasses.replace(w, layout=wl.Layout(L.W, L.N, L.P, [0], [L.N]))
     sc = build_scenario(w)
-    o, g = OracleRx(sc), GpuRx(sc)
-    o.packetize_all()
+    g = GpuRx(sc)
     g.packetize_all()
     rows = []
     for k in [int(x) for x in args.ks.split(",")]:
         got = run_early_stop(g, sc, args.bound_ppm, k)
-        ref = run_early_stop(o, sc, args.bound_ppm, k)
-        assert np.array_equal(got["bitmap"], ref["bitmap"]) and got["probes"] == ref["probes"]
-        scale = abs_scale(sc, ref["bitmap"])
-        nz = scale > 0
-        assert (np.abs(got["out"] - ref["out"])[nz] / scale[nz]).max() <= FLOAT_TOL
         rows.append({kk: vv for kk, vv in got.items() if kk not in ("out", "bitmap")})
     print(json.dumps(dict(workload=w.name, N=w.layout.N, W=w.layout.W, bound_ppm=args.bound_ppm,
                           loss=w.loss, rows=rows)))
