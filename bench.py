@@ -229,7 +229,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
-    ap.add_argument("--cpu-sample-elems", type=int, default=48_000_000)
+    ap.add_argument("--cpu-sample-elems", type=int, default=96_000_000)
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (all workers are simulated in that GPU's "
@@ -301,7 +301,7 @@ def main():
     achieved = g_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
     ratio_pmc = PMC_TRAFFIC_RATIO.get(_kernel_source_hash())
     roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=round(achieved / HBM_PEAK_GBPS, 4), kernel="gather_accumulate",
+                    frac=round(achieved / HBM_PEAK_GBPS, 4), kernel="gather_accumulate_staged",
                     launches=g_n, avg_launch_ms=round(g_ms / max(g_n, 1), 4),
                     algorithmic_bytes_per_launch=round(g_bytes / max(g_n, 1)),
                     traffic=None if ratio_pmc is None else round(ratio_pmc * g_bytes / max(g_n, 1)))

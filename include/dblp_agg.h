@@ -177,7 +177,8 @@ int dblp_get_prev_norm(const dblp_ctx* ctx, double* h_norm, int* h_have);
 /* Optional tracing: with profiling on, the launches of the kernels below are bracketed by
  * HIP events on the context's stream.  dblp_profile_read synchronises the stream, returns
  * the summed duration (milliseconds) and number of launches recorded for one kernel group
- * since the last read of that group, and forgets them. */
+ * since the last read of that group, and forgets them.  At most 16384 brackets are kept between
+ * reads; further ones are dropped.  dblp_profile_enable may return ENOMEM. */
 #define DBLP_K_INDEX 0    /* header parse / validation / arrival index */
 #define DBLP_K_GATHER 1   /* payload gather + accumulate */
 #define DBLP_K_PROBE 2    /* loss count + prefix + retransmit list (three launches, one bracket) */

@@ -2,22 +2,23 @@
 // Kernels and the C-ABI declared in include/dblp_agg.h.
 //
 // Data flow of one arrival batch (Alg. "DBLP_RECV", chunk-arrival branch):
-//   index_arrivals  one thread per arrival: header parse, validation, and an
-//                   atomicMin of (arrival rank << 32 | slot) into the arrival
-//                   index `pending[w][seq]`  (integer work, a few bytes per packet)
-//   gather_accumulate  one wave per run of consecutive sequence numbers: reads
-//                   the index, sets bitmap bits, then streams the payloads of
-//                   that packet from all workers (16-byte loads, worker order)
-//                   into registers and writes the accumulator span once.
-// Every payload byte is read exactly once and the accumulator is written once
-// per batch that touches it; there are no floating-point atomics, so the sum
-// is independent of the arrival permutation.
+//   index_arrivals   one thread per arrival: header parse, validation, and an atomicMin of
+//                    (arrival rank << 32 | slot) into the arrival index `pending[w][seq]`, so the
+//                    earliest copy of a packet in the batch wins; also the touched seq range
+//   gather_accumulate_staged / gather_accumulate
+//                    organised by OUTPUT packet: a block takes a group of consecutive sequence
+//                    numbers, reads the index entries of all workers, drops copies of packets
+//                    that an earlier batch delivered, sets the bitmap bits, then streams the
+//                    payloads of each packet from every delivering worker (16-byte loads,
+//                    worker order) into registers and writes the accumulator span once.
+// Every payload byte is read exactly once and the accumulator is written once per batch that
+// touches it; there are no floating-point atomics, so the sum is independent of the arrival
+// permutation.
 //
-// The probe (Sec. "Dynamically Changing Loss Tolerance"): loss_count (ballot-free
-// popcount of bitmap words + DPP wave reduction), scan_need (exclusive prefix of
-// the per-(worker,bucket) list lengths) and emit_retx (ordered compaction).
-// finalize_mean applies the zero-fill/mean of Alg. "Server" and produces the
-// partial sums of squares that Eq. 1 needs; reduce_partials finishes the norm.
+// The probe (Sec. "Dynamically Changing Loss Tolerance"): loss_count (popcount of bitmap words +
+// DPP wave reduction), scan_need (exclusive prefix of the per-(worker,bucket) list lengths) and
+// emit_retx (ordered compaction).  finalize_mean applies the zero-fill/mean of Alg. "Server" and
+// produces the partial sums of squares that Eq. 1 needs; reduce_partials finishes the norm.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -25,6 +26,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <new>
 #include <vector>
 
 #include "../../include/dblp_agg.h"
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
                                                       const u64* __restrict__ mask, const u32* __restrict__ order,
                                                       u64 n_arrivals, u32 cur_round, u64* __restrict__ pending,
                                                       u64* __restrict__ counters) {
-    __shared__ u32 sh[4][6];
+    __shared__ u32 sh[4][5];    // per wave: stale, invalid, candidates, lowest seq, highest seq + 1
     u32 n_stale = 0, n_inv = 0, n_cand = 0;
     u32 seq_lo = 0xFFFFFFFFu, seq_hi = 0;
     const u64 stride = (u64)gridDim.x * blockDim.x;
@@ -255,22 +257,22 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
     seq_lo = wave_reduce<OpMin>(seq_lo); seq_hi = wave_reduce<OpMax>(seq_hi);
     const u32 wave = threadIdx.x / WAVE;
     if (lane_id() == 0) {
-        sh[wave][0] = n_stale; sh[wave][1] = n_inv; sh[wave][2] = 0; sh[wave][3] = n_cand;
-        sh[wave][4] = seq_lo; sh[wave][5] = seq_hi;
+        sh[wave][0] = n_stale; sh[wave][1] = n_inv; sh[wave][2] = n_cand;
+        sh[wave][3] = seq_lo; sh[wave][4] = seq_hi;
     }
     __syncthreads();
     if (threadIdx.x == 0) {
-        u32 t[4] = {0, 0, 0, 0}, lo = 0xFFFFFFFFu, hi = 0;
+        u32 t[3] = {0, 0, 0}, lo = 0xFFFFFFFFu, hi = 0;
         for (int i = 0; i < 4; ++i) {
-            for (int j = 0; j < 4; ++j) t[j] += sh[i][j];
-            lo = sh[i][4] < lo ? sh[i][4] : lo;
-            hi = sh[i][5] > hi ? sh[i][5] : hi;
+            for (int j = 0; j < 3; ++j) t[j] += sh[i][j];
+            lo = sh[i][3] < lo ? sh[i][3] : lo;
+            hi = sh[i][4] > hi ? sh[i][4] : hi;
         }
         if (t[0]) atomicAdd(&counters[C_STALE], (u64)t[0]);
         if (t[1]) atomicAdd(&counters[C_INVALID], (u64)t[1]);
-        if (t[3]) {
-            atomicAdd(&counters[C_CANDIDATES], (u64)t[3]);
-            atomicAdd(&counters[C_BATCH_CAND], (u64)t[3]);
+        if (t[2]) {
+            atomicAdd(&counters[C_CANDIDATES], (u64)t[2]);
+            atomicAdd(&counters[C_BATCH_CAND], (u64)t[2]);
             // the range only widens: skip the atomic when a plain read shows it would not
             if ((u64)lo < *(volatile u64*)&counters[C_LO]) atomicMin(&counters[C_LO], (u64)lo);
             if ((u64)hi > *(volatile u64*)&counters[C_HI]) atomicMax(&counters[C_HI], (u64)hi);
@@ -903,7 +905,8 @@ struct ProfScope {
         hipEvent_t b = prof_event(c);
         if (!b) { c->ev_pool->push_back(a); return; }
         (void)hipEventRecord(b, c->stream);
-        c->timed->push_back({a, b, kernel});
+        if (c->timed->size() < c->timed->capacity()) c->timed->push_back({a, b, kernel});   // never reallocates
+        else { c->ev_pool->push_back(a); c->ev_pool->push_back(b); }                        // buffer full: drop the sample
     }
 };
 
@@ -1292,8 +1295,18 @@ extern "C" int dblp_get_counters(dblp_ctx* c, uint64_t h[4]) {
     return DBLP_OK;
 }
 
+#define PROF_MAX_RECORDS 16384   // brackets kept between two dblp_profile_read calls; more are dropped
+
 extern "C" int dblp_profile_enable(dblp_ctx* c, int on) {
     if (!c) return DBLP_EINVAL;
+    if (on) {
+        try {
+            c->timed->reserve(PROF_MAX_RECORDS);
+            c->ev_pool->reserve(2 * PROF_MAX_RECORDS + 64);
+        } catch (...) {
+            return fail(c, DBLP_ENOMEM, "profile_enable: out of host memory");
+        }
+    }
     c->profiling = on != 0;
     return DBLP_OK;
 }
@@ -1303,14 +1316,15 @@ extern "C" int dblp_profile_read(dblp_ctx* c, int kernel, double* h_total_ms, ui
     HIP_TRY(c, hipSetDevice(c->device));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     double total = 0.0; u64 n = 0;
-    std::vector<dblp_ctx::Timed> keep;
-    for (auto& t : *c->timed) {
-        if (t.kernel != kernel) { keep.push_back(t); continue; }
+    size_t kept = 0;                      // compact in place: no allocation on this path
+    for (size_t i = 0; i < c->timed->size(); ++i) {
+        const dblp_ctx::Timed t = (*c->timed)[i];
+        if (t.kernel != kernel) { (*c->timed)[kept++] = t; continue; }
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) { total += ms; ++n; } else (void)hipGetLastError();
-        c->ev_pool->push_back(t.a); c->ev_pool->push_back(t.b);
+        c->ev_pool->push_back(t.a); c->ev_pool->push_back(t.b);   // within the reserved capacity
     }
-    c->timed->swap(keep);
+    c->timed->resize(kept);
     *h_total_ms = total; *h_launches = n;
     return DBLP_OK;
 }
