@@ -137,12 +137,24 @@ __global__ __launch_bounds__(256) void fill_u64(u64* __restrict__ p, u64 n, u64 
     for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = v;
 }
 
-__global__ void reset_counters(u64* __restrict__ c, int keep_round_totals) {
+__global__ void reset_counters(u64* __restrict__ c) {
     u32 t = threadIdx.x;
     if (t >= C_COUNT) return;
-    if (t == C_LO) c[t] = NONE64;
-    else if (t == C_HI || t == C_BATCH_CAND) c[t] = 0;
-    else if (!keep_round_totals) c[t] = 0;
+    c[t] = t == C_LO ? NONE64 : 0;
+}
+
+// counters[C_ACCEPTED] = sum of the per-block rows written by the gather kernels.  One block.
+__global__ __launch_bounds__(256) void fold_accept_rows(const u64* __restrict__ rows, u32 n, u64* __restrict__ counters) {
+    __shared__ u64 sh[256];
+    u64 s = 0;
+    for (u32 i = threadIdx.x; i < n; i += 256) s += rows[i];
+    sh[threadIdx.x] = s;
+    __syncthreads();
+    for (u32 d = 128; d > 0; d >>= 1) {
+        if (threadIdx.x < d) sh[threadIdx.x] += sh[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) counters[C_ACCEPTED] = sh[0];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -222,13 +234,14 @@ __global__ __launch_bounds__(256) void packetize_list_kernel(Geo g, GradPtrs gra
 // receiver step 1: index the arrivals
 // ------------------------------------------------------------------------------------------
 // Grid-stride over arrivals.  Per-thread tallies are reduced per wave (DPP) and per block
-// (LDS); each block then issues at most one global atomic per counter, because atomics of many
-// waves on one address serialise in L2.
+// (LDS) and written to the block's row of block_tallies; fold_index_tallies adds the rows up.
+// No global atomics on shared counters: atomics of many waves (or even of a few thousand
+// blocks) on one address serialise in L2 at about 12 ns each.
 __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __restrict__ packets,
                                                       const uint16_t* __restrict__ src_worker, u64 n_slots,
                                                       const u64* __restrict__ mask, const u32* __restrict__ order,
                                                       u64 n_arrivals, u32 cur_round, u64* __restrict__ pending,
-                                                      u64* __restrict__ counters) {
+                                                      u32* __restrict__ block_tallies) {
     __shared__ u32 sh[4][5];    // per wave: stale, invalid, candidates, lowest seq, highest seq + 1
     u32 n_stale = 0, n_inv = 0, n_cand = 0;
     u32 seq_lo = 0xFFFFFFFFu, seq_hi = 0;
@@ -268,15 +281,42 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
             lo = sh[i][3] < lo ? sh[i][3] : lo;
             hi = sh[i][4] > hi ? sh[i][4] : hi;
         }
-        if (t[0]) atomicAdd(&counters[C_STALE], (u64)t[0]);
-        if (t[1]) atomicAdd(&counters[C_INVALID], (u64)t[1]);
-        if (t[2]) {
-            atomicAdd(&counters[C_CANDIDATES], (u64)t[2]);
-            atomicAdd(&counters[C_BATCH_CAND], (u64)t[2]);
-            // the range only widens: skip the atomic when a plain read shows it would not
-            if ((u64)lo < *(volatile u64*)&counters[C_LO]) atomicMin(&counters[C_LO], (u64)lo);
-            if ((u64)hi > *(volatile u64*)&counters[C_HI]) atomicMax(&counters[C_HI], (u64)hi);
+        u32* row = block_tallies + (u64)blockIdx.x * 5;
+        row[0] = t[0]; row[1] = t[1]; row[2] = t[2]; row[3] = lo; row[4] = hi;
+    }
+}
+
+// Folds the per-block tallies of one index launch into the context's counters: round totals are
+// added to, the batch's candidate count and touched seq range are set.  One block.
+__global__ __launch_bounds__(256) void fold_index_tallies(const u32* __restrict__ block_tallies, u32 n_blocks,
+                                                          u64* __restrict__ counters) {
+    __shared__ u32 sh[4][5];
+    u32 t0 = 0, t1 = 0, t2 = 0, lo = 0xFFFFFFFFu, hi = 0;
+    for (u32 b = threadIdx.x; b < n_blocks; b += 256) {
+        const u32* row = block_tallies + (u64)b * 5;
+        t0 += row[0]; t1 += row[1]; t2 += row[2];
+        lo = row[3] < lo ? row[3] : lo;
+        hi = row[4] > hi ? row[4] : hi;
+    }
+    t0 = wave_reduce<OpAdd>(t0); t1 = wave_reduce<OpAdd>(t1); t2 = wave_reduce<OpAdd>(t2);
+    lo = wave_reduce<OpMin>(lo); hi = wave_reduce<OpMax>(hi);
+    const u32 wave = threadIdx.x / WAVE;
+    if (lane_id() == 0) { sh[wave][0] = t0; sh[wave][1] = t1; sh[wave][2] = t2; sh[wave][3] = lo; sh[wave][4] = hi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u64 s0 = 0, s1 = 0, s2 = 0;
+        u32 l = 0xFFFFFFFFu, h = 0;
+        for (int i = 0; i < 4; ++i) {
+            s0 += sh[i][0]; s1 += sh[i][1]; s2 += sh[i][2];
+            l = sh[i][3] < l ? sh[i][3] : l;
+            h = sh[i][4] > h ? sh[i][4] : h;
         }
+        counters[C_STALE] += s0;
+        counters[C_INVALID] += s1;
+        counters[C_CANDIDATES] += s2;
+        counters[C_BATCH_CAND] = s2;
+        counters[C_LO] = s2 ? (u64)l : NONE64;
+        counters[C_HI] = s2 ? (u64)h : 0;
     }
 }
 
@@ -338,8 +378,8 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
 //            worker that delivered it, summed in registers in worker order, one write of the span
 __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
                                                                     u64* __restrict__ pending, u64* __restrict__ bitmap,
-                                                                    float* __restrict__ acc, u64* __restrict__ counters,
-                                                                    int only_if_sparse) {
+                                                                    float* __restrict__ acc, const u64* __restrict__ counters,
+                                                                    u64* __restrict__ accept_rows, int only_if_sparse) {
     extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB]
     __shared__ u64 sh_elem[SUB];
     __shared__ u32 sh_len[SUB];
@@ -423,7 +463,14 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
         }
         __syncthreads();                                     // LDS is reused by the next group
     }
-    if (lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
+    // accepted packets of this block: one plain add to the block's own row (no shared atomics)
+    if (lane == 0) sh_new[wave] = accepted;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 total = 0;
+        for (int i = 0; i < GA_WAVES; ++i) total += sh_new[i];
+        if (total) accept_rows[blockIdx.x] += total;
+    }
 }
 
 // Staged variant of the gather (used whenever two groups of packets fit in LDS).
@@ -480,7 +527,8 @@ __device__ __forceinline__ void sum_packet(const uint8_t* __restrict__ packets, 
 template <int NP>
 __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_staged(
     Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
-    float* __restrict__ acc, u64* __restrict__ counters, u32 sub, u32 sub_log2, u32 n_pass) {
+    float* __restrict__ acc, const u64* __restrict__ counters, u64* __restrict__ accept_rows, u32 sub, u32 sub_log2,
+    u32 n_pass) {
     extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, then slots
     __shared__ u64 sh_elem[2][SUB];
     __shared__ u32 sh_len[2][SUB];
@@ -638,7 +686,14 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
         }
         __syncthreads();
     }
-    if (wave < n_readers && lane == 0 && accepted) atomicAdd(&counters[C_ACCEPTED], (u64)accepted);
+    // accepted packets of this block: one plain add to the block's own row (no shared atomics)
+    if (wave < n_readers && lane == 0) sh_new[wave] = accepted;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        u32 total = 0;
+        for (u32 i = 0; i < n_readers; ++i) total += sh_new[i];
+        if (total) accept_rows[blockIdx.x] += total;
+    }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -871,6 +926,8 @@ struct dblp_ctx {
     u32* d_first_seq; u64* d_b_off; u64* d_b_cnt;
     u64* d_bitmap; u64* d_pending; float* d_acc; u64* d_counters;
     u32* d_need; u32* d_missing; u64* d_offs; double* d_partials;
+    u32* d_block_tallies;   // [IDX_BLOCKS_PER_CU * n_cus][5], written by index_arrivals
+    u64* d_accept_rows;     // [2][ACCEPT_ROWS] accepted packets per gather block (staged grid, direct grid)
     u64* h_mailbox;         // pinned host memory, 8 x u64, also mapped into the device
     u64* d_mailbox;         // device address of h_mailbox
     // host copies of the geometry
@@ -945,7 +1002,7 @@ extern "C" int dblp_destroy(dblp_ctx* c) {
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
     void* dev[] = {c->d_first_seq, c->d_b_off, c->d_b_cnt, c->d_bitmap, c->d_pending, c->d_acc,
-                   c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials};
+                   c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials, c->d_block_tallies, c->d_accept_rows};
     for (void* p : dev) if (p) (void)hipFree(p);
     if (c->h_mailbox) (void)hipHostFree(c->h_mailbox);
     if (c->timed) { for (auto& t : *c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); } delete c->timed; }
@@ -956,6 +1013,10 @@ extern "C" int dblp_destroy(dblp_ctx* c) {
 }
 
 #define FIN_BLOCKS_PER_CU 8
+#define ACCEPT_ROWS 8192   // >= blocks of any gather launch (n_cus * blocks per CU)
+#ifndef IDX_BLOCKS_PER_CU
+#define IDX_BLOCKS_PER_CU 8
+#endif
 
 extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     if (!out || !cfg || !cfg->buckets) return DBLP_EINVAL;
@@ -1005,6 +1066,7 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     e = hipGetDeviceProperties(&prop, c->device);
     if (e != hipSuccess) { dblp_destroy(c); return DBLP_EHIP; }
     c->n_cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if ((u64)c->n_cus * 16 > ACCEPT_ROWS) c->n_cus = ACCEPT_ROWS / 16;   // grids are sized n_cus x (<= 16) blocks
 
     const u64 pairs = (u64)g.W * B;
     const u32 max_partials = (u32)c->n_cus * FIN_BLOCKS_PER_CU;
@@ -1020,6 +1082,8 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     ok = ok && hipMalloc(&c->d_missing, pairs * sizeof(u32)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_offs, pairs * sizeof(u64)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_partials, max_partials * sizeof(double)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_accept_rows, 2 * ACCEPT_ROWS * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_block_tallies, (size_t)c->n_cus * IDX_BLOCKS_PER_CU * 5 * sizeof(u32)) == hipSuccess;
     ok = ok && hipHostMalloc((void**)&c->h_mailbox, 8 * sizeof(u64), hipHostMallocMapped) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); dblp_destroy(c); return DBLP_ENOMEM; }
     ok = ok && hipHostGetDevicePointer((void**)&c->d_mailbox, c->h_mailbox, 0) == hipSuccess;
@@ -1034,7 +1098,8 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
                        c->d_pending, n_pending, NONE64);
     hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (g.W * g.words_pw + 255) / 256, 16)), dim3(256), 0, c->stream,
                        c->d_bitmap, g.W * g.words_pw, 0ull);
-    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters, 0);
+    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters);
+    hipLaunchKernelGGL(fill_u64, dim3(32), dim3(256), 0, c->stream, c->d_accept_rows, (u64)(2 * ACCEPT_ROWS), 0ull);
     e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess || hipGetLastError() != hipSuccess) { dblp_destroy(c); return DBLP_EHIP; }
     c->err[0] = 0;
@@ -1055,7 +1120,8 @@ extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
     HIP_TRY(c, hipSetDevice(c->device));
     const u64 n = c->g.W * c->g.words_pw;
     hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n + 255) / 256, 16)), dim3(256), 0, c->stream, c->d_bitmap, n, 0ull);
-    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters, 0);
+    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters);
+    hipLaunchKernelGGL(fill_u64, dim3(32), dim3(256), 0, c->stream, c->d_accept_rows, (u64)(2 * ACCEPT_ROWS), 0ull);
     LAUNCH_CHECK(c, "begin_round");
     c->round = round; c->round_open = 1; c->finalized = 0;
     return DBLP_OK;
@@ -1148,12 +1214,13 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
     if (!d_order && n_arrivals > n_slots) return fail(c, DBLP_EINVAL, "apply_arrivals: identity order longer than the buffer");
     HIP_TRY(c, hipSetDevice(c->device));
     const Geo& g = c->g;
-    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters, 1);
     {
         ProfScope ps(c, DBLP_K_INDEX);
-        hipLaunchKernelGGL(index_arrivals, dim3(grid_for(c, (n_arrivals + 255) / 256, 8)), dim3(256), 0, c->stream, g,
-                           (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
-                           (u64)n_arrivals, (u32)c->round, c->d_pending, c->d_counters);
+        const u32 grid = grid_for(c, (n_arrivals + 255) / 256, IDX_BLOCKS_PER_CU);
+        hipLaunchKernelGGL(index_arrivals, dim3(grid), dim3(256), 0, c->stream, g, (const uint8_t*)d_packets,
+                           d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order, (u64)n_arrivals, (u32)c->round,
+                           c->d_pending, c->d_block_tallies);
+        hipLaunchKernelGGL(fold_index_tallies, dim3(1), dim3(256), 0, c->stream, c->d_block_tallies, grid, c->d_counters);
     }
     {
         ProfScope ps(c, DBLP_K_GATHER);
@@ -1169,20 +1236,20 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
             if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
             if (per_cu > GS_MAX_PER_CU) per_cu = GS_MAX_PER_CU;
             if (per_cu < 1) per_cu = 1;
-            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, u64*, u32, u32, u32) =
+            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, const u64*, u64*, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
             hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, per_cu)), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
-                               c->d_counters, sub, sub_log2, n_pass);
+                               c->d_counters, c->d_accept_rows, sub, sub_log2, n_pass);
         }
         {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
             const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
             hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
-                               c->d_counters, sub >= 2 ? 1 : 0);
+                               c->d_counters, c->d_accept_rows + ACCEPT_ROWS, sub >= 2 ? 1 : 0);
         }
     }
     LAUNCH_CHECK(c, "apply_arrivals");
@@ -1286,6 +1353,9 @@ extern "C" int dblp_get_counters(dblp_ctx* c, uint64_t h[4]) {
     if (!c || !h) return DBLP_EINVAL;
     HIP_TRY(c, hipSetDevice(c->device));
     u64 tmp[C_COUNT];
+    hipLaunchKernelGGL(fold_accept_rows, dim3(1), dim3(256), 0, c->stream, c->d_accept_rows, (u32)(2 * ACCEPT_ROWS),
+                       c->d_counters);
+    LAUNCH_CHECK(c, "get_counters");
     HIP_TRY(c, hipMemcpyAsync(tmp, c->d_counters, sizeof tmp, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     h[0] = tmp[C_ACCEPTED];
