@@ -106,6 +106,16 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
     return __longlong_as_double((long long)(((u64)hi << 32) | lo));
 }
 
+// 16-byte load with the non-temporal hint: the payload is read exactly once, so it should not
+// displace the accumulator and index lines that are being written in L2 / the memory-side cache
+// (measured: 8 % off the payload pass).  Headers are NOT loaded this way in the index pass:
+// their lines are read again by the payload pass and are worth keeping.
+typedef float f4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 ld_stream4(const void* p) {
+    const f4v t = __builtin_nontemporal_load((const f4v*)p);
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
 __device__ __forceinline__ u32 lane_id() { return threadIdx.x & (WAVE - 1); }
 
 // ------------------------------------------------------------------------------------------
@@ -512,7 +522,7 @@ __device__ __forceinline__ void sum_packet(const uint8_t* __restrict__ packets, 
                 const uint8_t* base = packets + (u64)slot * stride + 16ull * lane;
                 #pragma unroll
                 for (int q = 0; q < NP; ++q)
-                    if (q * WAVE + lane < units) v[j][q] = *(const float4*)(base + 1024ull * q);
+                    if (q * WAVE + lane < units) v[j][q] = ld_stream4(base + 1024ull * q);
             }
         }
         #pragma unroll
