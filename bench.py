@@ -49,7 +49,7 @@ def log(*a):
 class DeviceJob:
     """One workload with every input resident in HBM, driven through the C-ABI binding."""
 
-    def __init__(self, w, n_masks: int, place: str | None = None, order: str | None = None,
+    def __init__(self, w, n_masks: int, place: str | None = None, order: str | None = None, queue: bool = True,
                  drawn_rounds: int = BENCH_DRAWN_ROUNDS, per_iteration_retx: bool = False):
         """drawn_rounds: retransmission rounds whose loss is drawn once (keyed to iteration 0) and kept
         on the device.  per_iteration_retx: draw every retransmission round's loss for the iteration
@@ -60,6 +60,7 @@ class DeviceJob:
         self.torch, self.wl, self.w = torch, wl, w
         L = self.L = w.layout
         self.place, self.order = place or w.place, order or w.order
+        self.queue = queue   # first transmissions handed over as receive queues (else mask + order + worker table)
         self.rnd_id = 1
         self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5))
         self.n_slots = L.W * L.n_pkts
@@ -131,8 +132,22 @@ class DeviceJob:
         d_s = torch.from_numpy(surv.reshape(-1)).cuda()
         by_slot = torch.zeros(self.n_slots, dtype=torch.uint8, device="cuda")
         by_slot[self.d_slot_of.long()] = d_s
+        lost = int(surv.size - int(surv.sum()))
+        if self.queue:
+            return dict(queues=[self._queue_for(ch, by_slot[ch["base"]: ch["base"] + ch["n"]]) for ch in self.chunks],
+                        lost=lost)
         out = [self._pack_bits(by_slot[ch["base"]: ch["base"] + ch["n"]]) for ch in self.chunks]
-        return dict(words=out, lost=int(surv.size - int(surv.sum())))
+        return dict(words=out, lost=lost)
+
+    def _queue_for(self, ch, alive):
+        """Receive queue of one chunk step: slot | worker << 32 for every packet that survived,
+        in arrival order (what the mask, the order and the per-slot worker table say together)."""
+        torch = self.torch
+        o = ch["d_order"]
+        slots = torch.arange(ch["n"], device="cuda") if o is None else o.long()
+        slots = slots[alive[slots].bool()]
+        worker = self.src[ch["base"]: ch["base"] + ch["n"]][slots].long() & 0xFFFF
+        return slots | (worker << 32)
 
     # -- the timed path --------------------------------------------------------------------
     def step(self, it: int, bound_ppm: int, scale_ratio: float = 1.0, record: list | None = None) -> dict:
@@ -144,9 +159,13 @@ class DeviceJob:
         st = L.stride
         m = self.masks[it % len(self.masks)]
         agg.begin_round(self.rnd_id)
-        for ch, words in zip(self.chunks, m["words"]):
-            agg.apply_arrivals(self.packets[ch["base"] * st:], self.src[ch["base"]:], ch["n"], words,
-                               ch["d_order"], ch["n"])
+        if self.queue:
+            for ch, q in zip(self.chunks, m["queues"]):
+                agg.apply_arrivals_queue(self.packets[ch["base"] * st:], ch["n"], q)
+        else:
+            for ch, words in zip(self.chunks, m["words"]):
+                agg.apply_arrivals(self.packets[ch["base"] * st:], self.src[ch["base"]:], ch["n"], words,
+                                   ch["d_order"], ch["n"])
         rounds, resent = 0, 0
         while True:
             count, met, trunc = agg.loss_account(bound_ppm, self.d_missing, self.d_list)
@@ -227,6 +246,9 @@ def main():
     ap.add_argument("--workload", default="cfg5", help="cfg1..cfg5 (default: the largest, cfg5)")
     ap.add_argument("--place", default=None, help="override wire placement: worker_major|interleave|shuffle")
     ap.add_argument("--order", default=None, help="override arrival order: identity|shuffle|reverse")
+    ap.add_argument("--arrivals", default="queue", choices=["queue", "tables"],
+                    help="how first transmissions are handed over: one receive queue of descriptors per "
+                         "chunk step (default), or mask + order + per-slot worker table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, "
@@ -245,7 +267,7 @@ def main():
     w = wl.workload(args.workload)
     L = w.layout
     total = args.warmup + args.steps
-    job = DeviceJob(w, n_masks=total, place=args.place, order=args.order)
+    job = DeviceJob(w, n_masks=total, place=args.place, order=args.order, queue=args.arrivals == "queue")
     agg = job.agg
     sched = w.scale_schedule
 
@@ -315,7 +337,7 @@ def main():
                config=dict(workload=f"{w.name}: W={L.W} N={L.N} P={L.P} buckets={L.B} "
                                     f"packets/round={L.W * L.n_pkts} loss={w.loss['kind']} "
                                     f"policy={w.policy['kind']}",
-                           placement=job.place, arrival_order=job.order,
+                           placement=job.place, arrival_order=job.order, arrivals=args.arrivals,
                            chunk_steps=len(job.chunks), resident_packet_GB=round(job.packets.numel() / 1e9, 2)),
                packets_per_s=round(accepted_total / wall, 1),
                path_hbm_frac=round(path_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),

@@ -136,6 +136,20 @@ int dblp_apply_arrivals(dblp_ctx* ctx, const void* d_packets, const uint16_t* d_
                         uint64_t n_slots, const uint64_t* d_mask_words, const uint32_t* d_order,
                         uint64_t n_arrivals);
 
+/* The same step (Alg. "DBLP_RECV", chunk-arrival branch) with the batch given as a receive
+ * queue: one 8-byte descriptor per datagram that actually arrived, in arrival order, as a
+ * receive loop sees them (each datagram comes with the address it was sent from).
+ *   d_queue       n_arrivals descriptors, 8-byte aligned:
+ *                 bits 0..31 slot of the packet in d_packets, bits 32..47 worker it came
+ *                 from, bits 48..63 zero.  Lost packets simply have no descriptor.
+ * Equivalent to dblp_apply_arrivals with d_order[k] = slot of descriptor k, d_src_worker taken
+ * from the descriptors and no mask, and classifies every arrival the same way (a descriptor
+ * with a non-zero reserved field, a worker >= n_workers or a slot >= n_slots is invalid).  It
+ * is the faster form: the descriptor is read coalesced, where the per-slot worker table and
+ * the mask cost a random access each.  Requires begin_round. */
+int dblp_apply_arrivals_queue(dblp_ctx* ctx, const void* d_packets, uint64_t n_slots,
+                              const uint64_t* d_queue, uint64_t n_arrivals);
+
 /* One probe (Alg. "DBLP_RECV" probe branch; Sec. "Dynamically Changing Loss Tolerance":
  * retransmission stops once missing/total <= p, and only lost packets are resent).
  * For every (worker w, bucket b): missing = packets of b not in w's bitmap; the pair meets

@@ -20,7 +20,7 @@ COMP_ZEROFILL_MEAN = 0
 K_INDEX, K_GATHER, K_PROBE, K_FINALIZE = 0, 1, 2, 3
 
 EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_begin_round", "dblp_packetize", "dblp_packetize_list",
-           "dblp_apply_arrivals", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
+           "dblp_apply_arrivals", "dblp_apply_arrivals_queue", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
            "dblp_get_bitmap", "dblp_get_counters", "dblp_set_prev_norm", "dblp_get_prev_norm",
            "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear", "dblp_clr_init", "dblp_clr_step"]
 
@@ -68,6 +68,7 @@ def lib():
         L.dblp_packetize.argtypes = [vp, u32, u16, vp, u64, u64, u64, u64, vp, u64, u64, vp, vp]
         L.dblp_packetize_list.argtypes = [vp, u16, ctypes.POINTER(vp), vp, u64, u64, u64, vp, vp]
         L.dblp_apply_arrivals.argtypes = [vp, vp, vp, u64, vp, vp, u64]
+        L.dblp_apply_arrivals_queue.argtypes = [vp, vp, u64, vp, u64]
         L.dblp_loss_account.argtypes = [vp, u32, vp, vp, u64, ctypes.POINTER(u64), ctypes.POINTER(i32)]
         L.dblp_finalize.argtypes = [vp, i32, vp]
         L.dblp_phase_signal.argtypes = [vp, vp, ctypes.POINTER(dbl), ctypes.POINTER(dbl), ctypes.POINTER(i32)]
@@ -186,6 +187,11 @@ class Aggregator:
             n_arrivals = d_order.numel() if d_order is not None else n_slots
         self._check(lib().dblp_apply_arrivals(self._h, _ptr(d_packets), _ptr(d_src_worker), n_slots,
                                               _ptr(d_mask_words), _ptr(d_order), n_arrivals))
+
+    def apply_arrivals_queue(self, d_packets, n_slots, d_queue, n_arrivals=None):
+        if n_arrivals is None:
+            n_arrivals = d_queue.numel()
+        self._check(lib().dblp_apply_arrivals_queue(self._h, _ptr(d_packets), n_slots, _ptr(d_queue), n_arrivals))
 
     def loss_account(self, bound_ppm, d_missing, d_retx_list, capacity=None):
         """Returns (count, all_met, truncated)."""

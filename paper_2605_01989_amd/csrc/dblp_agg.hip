@@ -247,32 +247,81 @@ __global__ __launch_bounds__(256) void packetize_list_kernel(Geo g, GradPtrs gra
 // (LDS) and written to the block's row of block_tallies; fold_index_tallies adds the rows up.
 // No global atomics on shared counters: atomics of many waves (or even of a few thousand
 // blocks) on one address serialise in L2 at about 12 ns each.
+#ifndef IDX_UNROLL
+#define IDX_UNROLL 1     // arrivals in flight per thread of the index kernel
+#endif
+//
+// TABLE_IN_LDS: the block first copies the bucket boundaries (first_seq, B + 1 words of dynamic
+// shared memory) into LDS, so the ten dependent steps of the bucket search stay inside the CU.
+// FROM_QUEUE: arrival k is the descriptor queue[k] = slot | worker << 32 (one coalesced 8-byte
+// load) instead of order[k], mask bit[slot] and src_worker[slot]; the latter two are random
+// accesses, and src_worker[slot] alone costs half as much as the header line it sits beside.
+template <bool TABLE_IN_LDS, bool FROM_QUEUE>
 __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __restrict__ packets,
                                                       const uint16_t* __restrict__ src_worker, u64 n_slots,
                                                       const u64* __restrict__ mask, const u32* __restrict__ order,
+                                                      const u64* __restrict__ queue,
                                                       u64 n_arrivals, u32 cur_round, u64* __restrict__ pending,
                                                       u32* __restrict__ block_tallies) {
     __shared__ u32 sh[4][5];    // per wave: stale, invalid, candidates, lowest seq, highest seq + 1
+    extern __shared__ u32 fs_lds[];
+    const u32* fs = g.first_seq;
+    if (TABLE_IN_LDS) {
+        for (u32 i = threadIdx.x; i <= g.B; i += blockDim.x) fs_lds[i] = g.first_seq[i];
+        __syncthreads();
+        fs = fs_lds;
+    }
     u32 n_stale = 0, n_inv = 0, n_cand = 0;
     u32 seq_lo = 0xFFFFFFFFu, seq_hi = 0;
     const u64 stride = (u64)gridDim.x * blockDim.x;
-    for (u64 k = (u64)blockIdx.x * blockDim.x + threadIdx.x; k < n_arrivals; k += stride) {
-        const u64 slot = order ? (u64)order[k] : k;
-        if (slot >= n_slots) { ++n_inv; continue; }
-        if (mask && !((mask[slot >> 6] >> (slot & 63)) & 1ull)) continue;   // lost: never looked at
-        const uint2 hdr = *(const uint2*)(packets + slot * g.stride);
-        const u32 seq = hdr.x, round = hdr.y & 0xFFFFu, len = hdr.y >> 16;
-        const u32 w = src_worker[slot];
-        if (round != cur_round) { ++n_stale; continue; }
-        if (w >= g.W || seq >= g.n_pkts) { ++n_inv; continue; }
-        const u32 b = find_bucket(g.first_seq, g.B, seq);
-        u64 elem; u32 want;
-        packet_span(g, seq, b, &elem, &want);
-        if (len != want) { ++n_inv; continue; }
-        ++n_cand;
-        atomicMin(&pending[(u64)w * g.n_pkts + seq], (k << 32) | slot);
-        seq_lo = seq < seq_lo ? seq : seq_lo;
-        seq_hi = seq + 1 > seq_hi ? seq + 1 : seq_hi;
+    // IDX_UNROLL arrivals per thread and trip: the loads of one stage (order, then mask word,
+    // header and worker) are issued for all of them before the first is used.
+    for (u64 k0 = (u64)blockIdx.x * blockDim.x + threadIdx.x; k0 < n_arrivals; k0 += IDX_UNROLL * stride) {
+        u64 slot[IDX_UNROLL];
+        bool live[IDX_UNROLL];
+        uint2 hdr[IDX_UNROLL];
+        u32 w[IDX_UNROLL];
+#pragma unroll
+        for (int j = 0; j < IDX_UNROLL; ++j) {
+            const u64 k = k0 + j * stride;
+            live[j] = k < n_arrivals;
+            if (FROM_QUEUE) {
+                const u64 e = live[j] ? queue[k] : 0;
+                slot[j] = e & 0xFFFFFFFFull;
+                w[j] = (u32)(e >> 32);      // bits 48..63 must be zero: w >= W below catches them
+            } else {
+                slot[j] = live[j] ? (order ? (u64)order[k] : k) : 0;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < IDX_UNROLL; ++j) {
+            if (live[j] && slot[j] >= n_slots) { ++n_inv; live[j] = false; }
+            // lost packets are never looked at
+            if (!FROM_QUEUE && live[j] && mask && !((mask[slot[j] >> 6] >> (slot[j] & 63)) & 1ull)) live[j] = false;
+        }
+#pragma unroll
+        for (int j = 0; j < IDX_UNROLL; ++j) {
+            if (live[j]) {
+                hdr[j] = *(const uint2*)(packets + slot[j] * g.stride);
+                if (!FROM_QUEUE) w[j] = src_worker[slot[j]];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < IDX_UNROLL; ++j) {
+            if (!live[j]) continue;
+            const u64 k = k0 + j * stride;
+            const u32 seq = hdr[j].x, round = hdr[j].y & 0xFFFFu, len = hdr[j].y >> 16;
+            if (round != cur_round) { ++n_stale; continue; }
+            if (w[j] >= g.W || seq >= g.n_pkts) { ++n_inv; continue; }
+            const u32 b = find_bucket(fs, g.B, seq);
+            u32 want = g.P;         // every packet of a bucket but its last one is full
+            if (seq + 1 == fs[b + 1]) { u64 elem; packet_span(g, seq, b, &elem, &want); }
+            if (len != want) { ++n_inv; continue; }
+            ++n_cand;
+            atomicMin(&pending[(u64)w[j] * g.n_pkts + seq], (k << 32) | slot[j]);
+            seq_lo = seq < seq_lo ? seq : seq_lo;
+            seq_hi = seq + 1 > seq_hi ? seq + 1 : seq_hi;
+        }
     }
     // loops above have lane-dependent trip counts; all 64 lanes are back here
     n_stale = wave_reduce<OpAdd>(n_stale); n_inv = wave_reduce<OpAdd>(n_inv);
@@ -1027,6 +1076,9 @@ extern "C" int dblp_destroy(dblp_ctx* c) {
 #ifndef IDX_BLOCKS_PER_CU
 #define IDX_BLOCKS_PER_CU 8
 #endif
+// Largest bucket-boundary table (bytes) the index kernel copies into LDS; with 8 blocks per CU
+// this keeps all of them resident in the CU's 160 KB.  Larger tables are searched in global memory.
+#define IDX_TABLE_LDS_MAX 16384u
 
 extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     if (!out || !cfg || !cfg->buckets) return DBLP_EINVAL;
@@ -1213,23 +1265,22 @@ extern "C" int dblp_packetize_list(dblp_ctx* c, uint16_t round, const float* con
     return DBLP_OK;
 }
 
-extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uint16_t* d_src_worker, uint64_t n_slots,
-                                   const uint64_t* d_mask, const uint32_t* d_order, uint64_t n_arrivals) {
-    if (!c) return DBLP_EINVAL;
-    if (!c->round_open) return fail(c, DBLP_ESTATE, "apply_arrivals before begin_round");
-    if (n_arrivals == 0) return DBLP_OK;
-    if (!d_packets || !d_src_worker) return fail(c, DBLP_EINVAL, "apply_arrivals: null pointer");
-    if (((uintptr_t)d_packets & 15) != 0) return fail(c, DBLP_EINVAL, "apply_arrivals: d_packets must be 16-byte aligned");
-    if (n_slots >= 0xFFFFFFFFull || n_arrivals >= 0xFFFFFFFFull) return fail(c, DBLP_EINVAL, "apply_arrivals: too many slots");
-    if (!d_order && n_arrivals > n_slots) return fail(c, DBLP_EINVAL, "apply_arrivals: identity order longer than the buffer");
+// Index pass + gather pass over one batch.  Exactly one of (d_src_worker [+ d_mask, d_order]) and
+// d_queue describes the arrivals.
+static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src_worker, uint64_t n_slots,
+                       const uint64_t* d_mask, const uint32_t* d_order, const uint64_t* d_queue, uint64_t n_arrivals) {
     HIP_TRY(c, hipSetDevice(c->device));
     const Geo& g = c->g;
     {
         ProfScope ps(c, DBLP_K_INDEX);
         const u32 grid = grid_for(c, (n_arrivals + 255) / 256, IDX_BLOCKS_PER_CU);
-        hipLaunchKernelGGL(index_arrivals, dim3(grid), dim3(256), 0, c->stream, g, (const uint8_t*)d_packets,
-                           d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order, (u64)n_arrivals, (u32)c->round,
-                           c->d_pending, c->d_block_tallies);
+        const size_t table = ((size_t)g.B + 1) * sizeof(u32);
+        void (*idx)(Geo, const uint8_t*, const uint16_t*, u64, const u64*, const u32*, const u64*, u64, u32, u64*, u32*) =
+            table <= IDX_TABLE_LDS_MAX ? (d_queue ? index_arrivals<true, true> : index_arrivals<true, false>)
+                                       : (d_queue ? index_arrivals<false, true> : index_arrivals<false, false>);
+        hipLaunchKernelGGL(idx, dim3(grid), dim3(256), table <= IDX_TABLE_LDS_MAX ? table : 0, c->stream, g,
+                           (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
+                           (const u64*)d_queue, (u64)n_arrivals, (u32)c->round, c->d_pending, c->d_block_tallies);
         hipLaunchKernelGGL(fold_index_tallies, dim3(1), dim3(256), 0, c->stream, c->d_block_tallies, grid, c->d_counters);
     }
     {
@@ -1265,6 +1316,30 @@ extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uin
     LAUNCH_CHECK(c, "apply_arrivals");
     c->finalized = 0;
     return DBLP_OK;
+}
+
+extern "C" int dblp_apply_arrivals(dblp_ctx* c, const void* d_packets, const uint16_t* d_src_worker, uint64_t n_slots,
+                                   const uint64_t* d_mask, const uint32_t* d_order, uint64_t n_arrivals) {
+    if (!c) return DBLP_EINVAL;
+    if (!c->round_open) return fail(c, DBLP_ESTATE, "apply_arrivals before begin_round");
+    if (n_arrivals == 0) return DBLP_OK;
+    if (!d_packets || !d_src_worker) return fail(c, DBLP_EINVAL, "apply_arrivals: null pointer");
+    if (((uintptr_t)d_packets & 15) != 0) return fail(c, DBLP_EINVAL, "apply_arrivals: d_packets must be 16-byte aligned");
+    if (n_slots >= 0xFFFFFFFFull || n_arrivals >= 0xFFFFFFFFull) return fail(c, DBLP_EINVAL, "apply_arrivals: too many slots");
+    if (!d_order && n_arrivals > n_slots) return fail(c, DBLP_EINVAL, "apply_arrivals: identity order longer than the buffer");
+    return apply_batch(c, d_packets, d_src_worker, n_slots, d_mask, d_order, nullptr, n_arrivals);
+}
+
+extern "C" int dblp_apply_arrivals_queue(dblp_ctx* c, const void* d_packets, uint64_t n_slots, const uint64_t* d_queue,
+                                         uint64_t n_arrivals) {
+    if (!c) return DBLP_EINVAL;
+    if (!c->round_open) return fail(c, DBLP_ESTATE, "apply_arrivals_queue before begin_round");
+    if (n_arrivals == 0) return DBLP_OK;
+    if (!d_packets || !d_queue) return fail(c, DBLP_EINVAL, "apply_arrivals_queue: null pointer");
+    if (((uintptr_t)d_packets & 15) != 0) return fail(c, DBLP_EINVAL, "apply_arrivals_queue: d_packets must be 16-byte aligned");
+    if (((uintptr_t)d_queue & 7) != 0) return fail(c, DBLP_EINVAL, "apply_arrivals_queue: d_queue must be 8-byte aligned");
+    if (n_slots >= 0xFFFFFFFFull || n_arrivals >= 0xFFFFFFFFull) return fail(c, DBLP_EINVAL, "apply_arrivals_queue: too many slots");
+    return apply_batch(c, d_packets, nullptr, n_slots, nullptr, nullptr, d_queue, n_arrivals);
 }
 
 extern "C" int dblp_loss_account(dblp_ctx* c, uint32_t bound_ppm, uint32_t* d_missing, uint64_t* d_retx_list,

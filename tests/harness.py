@@ -169,11 +169,13 @@ def _dev(a: np.ndarray, as_dtype):
 class GpuRx:
     """Drives the HIP library on device-resident packets built by its own packetize."""
 
-    def __init__(self, sc: Scenario, eta: float = 0.5):
+    def __init__(self, sc: Scenario, eta: float = 0.5, queue: bool = False):
+        """queue=True hands every batch over as a receive queue (dblp_apply_arrivals_queue): the
+        descriptors are built here, on the host, from the same (mask, order, per-slot worker)."""
         import torch
         import paper_2605_01989_amd as dblp
         L = sc.L
-        self.sc, self.torch = sc, torch
+        self.sc, self.torch, self.queue = sc, torch, queue
         self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, eta)
         assert (self.agg.n_pkts, self.agg.stride) == (L.n_pkts, L.stride)
         n_slots = L.W * L.n_pkts
@@ -200,8 +202,30 @@ class GpuRx:
     def begin_round(self, rnd_id):
         self.agg.begin_round(rnd_id)
 
+    def _descriptors(self, slot_base, n_slots, mask, order, n_arrivals):
+        """slot | worker << 32 per arrival that survived, in arrival order."""
+        if order is None:
+            slots = np.arange(n_slots if n_arrivals is None else n_arrivals, dtype=np.uint64)
+        else:
+            slots = np.asarray(order, dtype=np.uint64)[:n_arrivals]
+        inside = slots < n_slots
+        keep = np.ones(slots.size, dtype=bool)
+        if mask is not None:
+            s_in = slots[inside]
+            words = np.asarray(mask, dtype=np.uint64)
+            keep[inside] = ((words[s_in >> np.uint64(6)] >> (s_in & np.uint64(63))) & np.uint64(1)).astype(bool)
+        src = self.src[slot_base: slot_base + n_slots].cpu().numpy().view(np.uint16).astype(np.uint64)
+        worker = np.zeros(slots.size, dtype=np.uint64)
+        worker[inside] = src[slots[inside]]
+        return (slots | (worker << np.uint64(32)))[keep]
+
     def apply(self, slot_base, n_slots, mask, order, n_arrivals=None):
         st = self.agg.stride
+        if self.queue:
+            q = self._descriptors(slot_base, n_slots, mask, order, n_arrivals)
+            if q.size:
+                self.agg.apply_arrivals_queue(self.packets[slot_base * st:], n_slots, _dev(q, np.int64), q.size)
+            return
         d_mask = None if mask is None else _dev(mask, np.int64)
         d_order = None if order is None else _dev(np.asarray(order, dtype=np.uint32), np.int32)
         if order is not None and n_arrivals is None:

@@ -133,6 +133,17 @@ def test_cfg5_full_size_sampled_buckets_and_global_properties():
         worst = max(worst, rel)
     print(f"cfg5 full size: rounds={res['rounds']} first list={first['count']} accepted={counters['accepted']} "
           f"sampled buckets={sample} worst float rel={worst:.2e}")
+    # --- the other hand-over form (mask + order + per-slot worker table instead of receive queues)
+    # must give the same bits: the sum over workers is formed in worker order either way
+    first_out = job.d_out.clone()
+    job.queue = False
+    job.masks = [job._mask_for(0)]
+    res2 = job.step(0, BOUND_PPM)
+    assert job.agg.get_counters() == counters and res2["rounds"] == res["rounds"] and res2["norm"] == res["norm"]
+    bitmap2 = torch.empty_like(bitmap)
+    job.agg.get_bitmap(bitmap2)
+    assert torch.equal(bitmap, bitmap2)
+    assert torch.equal(first_out.view(torch.int32), job.d_out.view(torch.int32))
     _SURVIVE.clear()
-    del job, bitmap
+    del job, bitmap, bitmap2, first_out
     torch.cuda.empty_cache()

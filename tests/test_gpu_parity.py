@@ -20,15 +20,15 @@ def mk(W, sizes, P, loss=0.0, seed=7, place="shuffle", order="shuffle", name="t"
                        place, order, dict(kind="fixed", ppm=0), seed=seed)
 
 
-def both(sc):
-    o, g = OracleRx(sc), GpuRx(sc)
+def both(sc, queue=False):
+    o, g = OracleRx(sc), GpuRx(sc, queue=queue)
     o.packetize_all()
     g.packetize_all()
     return o, g
 
 
-def run_both(sc, ppm):
-    o, g = both(sc)
+def run_both(sc, ppm, queue=False):
+    o, g = both(sc, queue)
     ref = run_iteration(o, sc, ppm)
     got = run_iteration(g, sc, ppm)
     return compare_results(got, ref, sc), got, ref
@@ -83,6 +83,23 @@ def test_parity_small_and_ragged(W, sizes, P, loss, ppm):
     assert stats["rel_to_addends"] <= FLOAT_TOL
 
 
+@pytest.mark.parametrize("W,sizes,P,loss,ppm", CASES)
+def test_parity_small_and_ragged_receive_queue(W, sizes, P, loss, ppm):
+    """The same cases with every batch handed over as a receive queue of descriptors."""
+    stats, got, ref = run_both(build_scenario(mk(W, sizes, P, loss)), ppm, queue=True)
+    assert stats["rel_to_addends"] <= FLOAT_TOL
+
+
+@pytest.mark.parametrize("queue", [False, True])
+def test_more_buckets_than_the_on_chip_table_holds(queue):
+    """5000 small buckets: the bucket boundaries no longer fit the index kernel's on-chip copy
+    and are searched in device memory."""
+    rng = np.random.default_rng(5)
+    sizes = [int(x) for x in rng.integers(1, 40, size=5000)]
+    stats, got, ref = run_both(build_scenario(mk(3, sizes, 7, 0.1)), 100_000, queue=queue)
+    assert stats["rel_to_addends"] <= FLOAT_TOL
+
+
 @pytest.mark.parametrize("place,order", [("worker_major", "identity"), ("worker_major", "reverse"),
                                          ("interleave", "identity"), ("shuffle", "shuffle")])
 def test_result_is_bitwise_independent_of_arrival_permutation(place, order):
@@ -110,7 +127,8 @@ def test_zero_loss_equals_fp32_sequential_mean_exactly():
     assert res["rounds"] == 0 and res["probes"][0]["met"]
 
 
-def test_multiple_batches_accumulate_into_existing_spans():
+@pytest.mark.parametrize("queue", [False, True])
+def test_multiple_batches_accumulate_into_existing_spans(queue):
     """Arrivals delivered in three separate batches, workers interleaved: later batches add to
     spans that earlier batches wrote (read-modify-write path) and never double count."""
     sc = build_scenario(mk(6, [366 * 90 + 11, 2000], 366, 0.1, place="worker_major", order="identity"))
@@ -118,7 +136,7 @@ def test_multiple_batches_accumulate_into_existing_spans():
     n = L.W * L.n_pkts
     rng = np.random.default_rng(3)
     part = rng.integers(0, 3, size=n)
-    o, g = both(sc)
+    o, g = both(sc, queue)
     for rx in (o, g):
         rx.begin_round(sc.rnd_id)
         for k in range(3):
@@ -136,9 +154,10 @@ def test_multiple_batches_accumulate_into_existing_spans():
     assert (np.abs(got - ref)[nz] / scale[nz]).max() <= FLOAT_TOL and np.all(got[~nz] == 0)
 
 
-def test_stale_duplicate_and_invalid_packets():
+@pytest.mark.parametrize("queue", [False, True])
+def test_stale_duplicate_and_invalid_packets(queue):
     sc = build_scenario(mk(2, [100, 7], 10, place="worker_major", order="identity"))
-    o, g = both(sc)
+    o, g = both(sc, queue)
     p = o.packets.reshape(-1, sc.L.stride)
     p[0, 0:4] = np.frombuffer(np.uint32(11).tobytes(), np.uint8)        # seq out of range
     p[1, 6:8] = np.frombuffer(np.uint16(9).tobytes(), np.uint8)         # wrong length
@@ -156,10 +175,11 @@ def test_stale_duplicate_and_invalid_packets():
     assert np.allclose(g.finalize(), o.finalize(), rtol=1e-6, atol=0)
 
 
-def test_first_arrival_of_conflicting_copies_wins():
+@pytest.mark.parametrize("queue", [False, True])
+def test_first_arrival_of_conflicting_copies_wins(queue):
     """Two slots claim the same (worker, seq) with different payloads: the earlier arrival is used."""
     sc = build_scenario(mk(1, [40], 10, place="worker_major", order="identity"))
-    o, g = both(sc)
+    o, g = both(sc, queue)
     p = o.packets.reshape(-1, sc.L.stride)
     p[3, :8] = p[2, :8]                     # slot 3 now also claims seq 2 (with seq 3's payload)
     g.upload_packets(o.packets, o.src)
@@ -223,6 +243,34 @@ def test_empty_batch_and_nothing_received():
     assert np.array_equal(mo, mg) and np.array_equal(lo, lg) and co == cg == 200
     assert not g.finalize().any()
     assert g.phase_signal()[0] == 0.0
+
+
+def test_receive_queue_descriptor_fields():
+    """Reserved bits, a worker or a slot out of range make a descriptor invalid; nothing else of
+    the batch is disturbed."""
+    import torch
+    from paper_2605_01989_amd import DblpError, binding
+    sc = build_scenario(mk(2, [100], 10, place="worker_major", order="identity"))
+    o, g = both(sc, queue=True)
+    q = np.arange(20, dtype=np.uint64) | (np.repeat(np.arange(2, dtype=np.uint64), 10) << np.uint64(32))
+    bad = np.array([q[4] | np.uint64(1) << np.uint64(48),      # reserved bit
+                    np.uint64(5) | np.uint64(2) << np.uint64(32),      # worker 2 of 2
+                    np.uint64(20) | np.uint64(1) << np.uint64(32),     # slot 20 of 20
+                    q[7]], dtype=np.uint64)                            # a plain duplicate
+    d_q = torch.from_numpy(np.concatenate([q, bad]).view(np.int64)).cuda()
+    g.begin_round(sc.rnd_id)
+    g.agg.apply_arrivals_queue(g.packets, 20, d_q)
+    assert g.counters() == dict(accepted=20, duplicate=1, stale=0, invalid=3)
+    o.begin_round(sc.rnd_id)
+    o.apply(0, 20, None, None)
+    assert np.array_equal(g.bitmap(), o.bitmap())
+    assert np.array_equal(g.finalize().astype(np.float64), o.finalize().astype(np.float32).astype(np.float64))
+    with pytest.raises(DblpError) as e:
+        g.agg.apply_arrivals_queue(g.packets, 20, None, 5)
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(DblpError) as e:
+        g.agg.apply_arrivals_queue(g.packets, 20, d_q.view(torch.int32)[1:], 5)     # misaligned queue
+    assert e.value.code == binding.EINVAL
 
 
 def test_api_errors():
