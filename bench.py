@@ -50,6 +50,7 @@ class DeviceJob:
     """One workload with every input resident in HBM, driven through the C-ABI binding."""
 
     def __init__(self, w, n_masks: int, place: str | None = None, order: str | None = None, queue: bool = True,
+                 accumulator: str = "auto",
                  drawn_rounds: int = BENCH_DRAWN_ROUNDS, per_iteration_retx: bool = False):
         """drawn_rounds: retransmission rounds whose loss is drawn once (keyed to iteration 0) and kept
         on the device.  per_iteration_retx: draw every retransmission round's loss for the iteration
@@ -63,6 +64,8 @@ class DeviceJob:
         self.queue = queue   # first transmissions handed over as receive queues (else mask + order + worker table)
         self.rnd_id = 1
         self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5))
+        if accumulator == "one":         # for comparison: no second accumulator copy
+            self.agg.accumulator_copies(1)
         self.n_slots = L.W * L.n_pkts
         dev = "cuda"
         t0 = time.time()
@@ -249,6 +252,9 @@ def main():
     ap.add_argument("--arrivals", default="queue", choices=["queue", "tables"],
                     help="how first transmissions are handed over: one receive queue of descriptors per "
                          "chunk step (default), or mask + order + per-slot worker table")
+    ap.add_argument("--accumulator", default="auto", choices=["auto", "one"],
+                    help="auto: the library's default (two accumulator copies in different thirds of HBM for "
+                         "large workloads); one: a single copy")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, "
@@ -267,7 +273,8 @@ def main():
     w = wl.workload(args.workload)
     L = w.layout
     total = args.warmup + args.steps
-    job = DeviceJob(w, n_masks=total, place=args.place, order=args.order, queue=args.arrivals == "queue")
+    job = DeviceJob(w, n_masks=total, place=args.place, order=args.order, queue=args.arrivals == "queue",
+                    accumulator=args.accumulator)
     agg = job.agg
     sched = w.scale_schedule
 
@@ -331,6 +338,8 @@ def main():
                     traffic=None if ratio_pmc is None else round(ratio_pmc * g_bytes / max(g_n, 1)))
     # whole-path algorithmic bytes: + finalize (read acc, write out) per iteration
     path_bytes = g_bytes + args.steps * 8 * L.N
+    acc_info = agg.accumulator_info()
+    acc_info.pop("last_pick")
     out = dict(metric="aggregated_gradient_GBps", value=round(value, 2), unit="GB/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 3),
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
@@ -338,6 +347,7 @@ def main():
                                     f"packets/round={L.W * L.n_pkts} loss={w.loss['kind']} "
                                     f"policy={w.policy['kind']}",
                            placement=job.place, arrival_order=job.order, arrivals=args.arrivals,
+                           accumulator=acc_info,
                            chunk_steps=len(job.chunks), resident_packet_GB=round(job.packets.numel() / 1e9, 2)),
                packets_per_s=round(accepted_total / wall, 1),
                path_hbm_frac=round(path_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),

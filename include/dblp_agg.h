@@ -90,6 +90,40 @@ int dblp_destroy(dblp_ctx* ctx);
 int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* packet_stride_bytes,
                 uint64_t* bitmap_words_per_worker);
 
+/* The accumulator and where it lives.  Not in the paper: a property of this memory system.
+ * A payload stream with a few percent of result writes mixed in runs about 15 % slower on
+ * MI355X when reads and writes fall into the same third of the HBM address space than when
+ * they fall into different thirds.  The library can keep the accumulator (N floats) in two
+ * copies in different thirds; the spans a batch writes for the first time go to the copy that
+ * is faster for that batch's packet buffer, later batches update a span where it lives, and
+ * dblp_finalize reads each span from its copy.  Results do not depend on any of this.
+ *
+ * dblp_create chooses two copies when one round carries at least 2 GiB of packets, else one.
+ * dblp_accumulator_copies(copies = 1|2, place): reallocates.  place != 0: search for a second
+ *   copy in another third than the first: candidates are allocated 8 GiB apart and timed
+ *   against the first copy until one differs (temporarily holds up to half of the device
+ *   memory; takes from 0.2 s on a fresh device to a few seconds); if none is found there is
+ *   no second copy.  place == 0: plain second allocation, kept regardless.  Synchronises the stream; discards
+ *   the round in progress (call dblp_begin_round again).  ENOMEM if not even one copy fits.
+ * dblp_accumulator_policy: DBLP_ACC_AUTO (default) times a read+write probe kernel on the
+ *   first batch seen from each packet buffer of at least 1 GiB (about 3 ms once per buffer,
+ *   synchronising the stream; the probe reads d_packets[0 .. n_slots * stride) and nothing
+ *   else of the caller's) and remembers the answer for the last 32 buffers; smaller or thinly
+ *   used buffers use the first copy.  FIRST / SECOND force a copy, ALTERNATE switches on
+ *   every batch (for tests).
+ * dblp_accumulator_info: number of copies, whether they were measured to lie in different
+ *   thirds, the copy the last batch wrote new spans to, and the placement measurement itself
+ *   (placement_ms[0], [1]: probe time in ms writing to the first / second copy, 0 if not
+ *   taken; [2]: candidates the placement search tried).  Any pointer may be NULL. */
+#define DBLP_ACC_AUTO 0
+#define DBLP_ACC_FIRST 1
+#define DBLP_ACC_SECOND 2
+#define DBLP_ACC_ALTERNATE 3
+int dblp_accumulator_copies(dblp_ctx* ctx, int copies, int place);
+int dblp_accumulator_policy(dblp_ctx* ctx, int policy);
+int dblp_accumulator_info(const dblp_ctx* ctx, int* copies, int* distinct_thirds, int* last_pick,
+                          double placement_ms[3]);
+
 /* Alg. "DBLP_RECV", initialisation: empty bitmap, nothing received, counters zero; `round`
  * is the round counter that arriving packets must carry.  The accumulator is not cleared:
  * a packet's first arrival overwrites its span and dblp_finalize writes zeros for spans

@@ -18,8 +18,9 @@ _NAMES = {EINVAL: "DBLP_EINVAL", ENOMEM: "DBLP_ENOMEM", ECAPACITY: "DBLP_ECAPACI
           ESTATE: "DBLP_ESTATE", EHIP: "DBLP_EHIP"}
 COMP_ZEROFILL_MEAN = 0
 K_INDEX, K_GATHER, K_PROBE, K_FINALIZE = 0, 1, 2, 3
+ACC_AUTO, ACC_FIRST, ACC_SECOND, ACC_ALTERNATE = 0, 1, 2, 3
 
-EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_begin_round", "dblp_packetize", "dblp_packetize_list",
+EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_accumulator_copies", "dblp_accumulator_policy", "dblp_accumulator_info", "dblp_begin_round", "dblp_packetize", "dblp_packetize_list",
            "dblp_apply_arrivals", "dblp_apply_arrivals_queue", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
            "dblp_get_bitmap", "dblp_get_counters", "dblp_set_prev_norm", "dblp_get_prev_norm",
            "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear", "dblp_clr_init", "dblp_clr_step"]
@@ -65,6 +66,9 @@ def lib():
         L.dblp_destroy.argtypes = [vp]
         L.dblp_layout.argtypes = [vp, ctypes.POINTER(u64), ctypes.POINTER(u32), ctypes.POINTER(u64)]
         L.dblp_begin_round.argtypes = [vp, u16]
+        L.dblp_accumulator_copies.argtypes = [vp, i32, i32]
+        L.dblp_accumulator_policy.argtypes = [vp, i32]
+        L.dblp_accumulator_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(dbl)]
         L.dblp_packetize.argtypes = [vp, u32, u16, vp, u64, u64, u64, u64, vp, u64, u64, vp, vp]
         L.dblp_packetize_list.argtypes = [vp, u16, ctypes.POINTER(vp), vp, u64, u64, u64, vp, vp]
         L.dblp_apply_arrivals.argtypes = [vp, vp, vp, u64, vp, vp, u64]
@@ -181,6 +185,18 @@ class Aggregator:
         ptrs = (ctypes.c_void_p * self.W)(*[t.data_ptr() for t in d_grads])
         self._check(lib().dblp_packetize_list(self._h, rnd & 0xFFFF, ptrs, _ptr(d_retx_list), n_entries, slot_base,
                                               n_slots, _ptr(d_packets), _ptr(d_src_worker)))
+
+    def accumulator_copies(self, copies: int, place: bool = False):
+        self._check(lib().dblp_accumulator_copies(self._h, copies, int(place)))
+
+    def accumulator_policy(self, policy: int):
+        self._check(lib().dblp_accumulator_policy(self._h, policy))
+
+    def accumulator_info(self) -> dict:
+        n, d, p, ms = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), (ctypes.c_double * 3)()
+        self._check(lib().dblp_accumulator_info(self._h, ctypes.byref(n), ctypes.byref(d), ctypes.byref(p), ms))
+        return dict(copies=n.value, distinct_thirds=bool(d.value), last_pick=p.value,
+                    placement_ms=[round(ms[0], 4), round(ms[1], 4)], placement_steps=int(ms[2]))
 
     def apply_arrivals(self, d_packets, d_src_worker, n_slots, d_mask_words=None, d_order=None, n_arrivals=None):
         if n_arrivals is None:

@@ -435,9 +435,15 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
 //            entries reset; the 16 packets' element spans are computed by 16 lanes in parallel
 //   phase B  the waves split the 16 packets: per packet, 16-byte payload loads from every
 //            worker that delivered it, summed in registers in worker order, one write of the span
+//
+// The accumulator may exist in two copies (acc0, acc1; acc1 == acc0 when there is one): a span
+// written for the first time in this round goes to copy `pick` and home[seq] records it; a span
+// that earlier batches wrote is read and rewritten where home[seq] says it lives.
 __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
                                                                     u64* __restrict__ pending, u64* __restrict__ bitmap,
-                                                                    float* __restrict__ acc, const u64* __restrict__ counters,
+                                                                    float* acc0, float* acc1,
+                                                                    uint8_t* __restrict__ home, u32 pick,
+                                                                    const u64* __restrict__ counters,
                                                                     u64* __restrict__ accept_rows, int only_if_sparse) {
     extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB]
     __shared__ u64 sh_elem[SUB];
@@ -502,7 +508,10 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
             const u32 slot32 = lane < W ? sh_slot[lane * SUB + t] : NONE32;
             const u64 sub = __ballot(slot32 != NONE32);
             const u32 units = (len + 2 + 3) >> 2;            // 16-byte units holding header + payload
-            float* dst0 = acc + elem - 2;                    // float position i of the packet -> dst0[i]
+            u32 h = pick;
+            if (rmw) h = home[seq0 + t];
+            else if (lane == 0) home[seq0 + t] = (uint8_t)pick;
+            float* dst0 = (h ? acc1 : acc0) + elem - 2;      // float position i of the packet -> dst0[i]
             for (u32 u0 = 0; u0 < units; u0 += WAVE) {
                 const u32 u = u0 + lane;
                 const bool active = u < units;
@@ -586,11 +595,12 @@ __device__ __forceinline__ void sum_packet(const uint8_t* __restrict__ packets, 
 template <int NP>
 __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_staged(
     Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
-    float* __restrict__ acc, const u64* __restrict__ counters, u64* __restrict__ accept_rows, u32 sub, u32 sub_log2,
-    u32 n_pass) {
+    float* acc0, float* acc1, uint8_t* __restrict__ home, u32 pick,
+    const u64* __restrict__ counters, u64* __restrict__ accept_rows, u32 sub, u32 sub_log2, u32 n_pass) {
     extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, then slots
     __shared__ u64 sh_elem[2][SUB];
     __shared__ u32 sh_len[2][SUB];
+    __shared__ u32 sh_home[2][SUB];                 // accumulator copy each packet of the group goes to
     __shared__ u32 sh_flag_new[2];
     __shared__ u32 sh_new[GS_READERS], sh_old[GS_READERS];
     const u64 lo = counters[C_LO], hi = counters[C_HI];
@@ -663,6 +673,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                 const u64 elem = sh_elem[prev][t];
                 const u32 len = sh_len[prev][t];
                 const float* pk = src + t * (g.stride >> 2) + 2;   // payload float j at pk[j]
+                float* acc = sh_home[prev][t] ? acc1 : acc0;
                 const u64 c0 = elem >> 2, c1 = (elem + len - 1) >> 2;
                 for (u64 c = c0 + lane; c <= c1; c += WAVE) {
                     const u64 e0 = c << 2;
@@ -697,6 +708,11 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                     float4 a[NP > 0 ? NP : 1];
                     sum_packet<(NP > 0 ? NP : 1)>(packets, g.stride, lane, units, subm, slot32, a);
                     const bool rmw = (old_any >> t) & 1u;         // earlier batches already wrote this span
+                    u32 h = pick;
+                    if (rmw) h = home[seq0 + t];
+                    else if (lane == 0) home[seq0 + t] = (uint8_t)pick;
+                    if (lane == 0) sh_home[cur][t] = h;
+                    const float* acc = h ? acc1 : acc0;
                     #pragma unroll
                     for (int q = 0; q < (NP > 0 ? NP : 1); ++q) {
                         const u32 u = q * WAVE + lane;
@@ -728,9 +744,14 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                 const u32 slot32 = lane < W ? sh_slot[lane * sub + t] : NONE32;
                 const u64 subm = __ballot(slot32 != NONE32);
                 float4 a = sum_unit(packets, g.stride, u, active, subm, slot32);
-                if (active && ((old_any >> t) & 1u)) {
+                const bool rmw = (old_any >> t) & 1u;
+                u32 h = pick;                       // every pass of packet t derives and records the same value
+                if (rmw) h = home[seq0 + t];
+                else if (lane == 0) home[seq0 + t] = (uint8_t)pick;
+                if (lane == 0) sh_home[cur][t] = h;
+                if (active && rmw) {
                     // earlier batches already wrote this span: result = old value + this batch's sum
-                    const float* o = acc + sh_elem[cur][t] - 2 + 4 * u;   // packet float position 4u+c -> o[c]
+                    const float* o = (h ? acc1 : acc0) + sh_elem[cur][t] - 2 + 4 * u;   // packet float position 4u+c -> o[c]
                     float q[4] = {a.x, a.y, a.z, a.w};
                     #pragma unroll
                     for (int c = 0; c < 4; ++c) {
@@ -866,7 +887,9 @@ __device__ __forceinline__ float scale_mean(float v, float inv_w, int use_div, f
 // A tile of 8 packets inside one bucket is one contiguous element range: it is walked in
 // 16-byte aligned chunks (float4 load, scale, float4 store); chunks that straddle a packet or
 // the range's ends, and tiles that cross a bucket boundary, go element by element.
-__global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restrict__ bitmap, const float* __restrict__ acc,
+// home[seq] (padded to a multiple of 8 entries) names the accumulator copy that holds the packet's span.
+__global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restrict__ bitmap, const float* acc0,
+                                                     const float* acc1, const uint8_t* __restrict__ home,
                                                      float* __restrict__ out, float inv_w, int use_div, float wf,
                                                      double* __restrict__ partials) {
     __shared__ double wsum[4];
@@ -883,6 +906,7 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
         u64 any = 0;
         for (u32 w = 0; w < g.W; ++w) any |= bitmap[(u64)w * g.words_pw + (seq0 >> 6)];
         any >>= (seq0 & 63);
+        const u64 hm = *(const u64*)(home + seq0);          // byte t = copy of packet seq0 + t (valid where `any` has bit t)
         u32 b = find_bucket(g.first_seq, g.B, seq0);
         if (seq0 + n_t <= g.first_seq[b + 1]) {
             const u64 elem0 = g.b_off[b] + (u64)(seq0 - g.first_seq[b]) * g.P;
@@ -896,7 +920,7 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
                 if (e0 >= elem0 && e0 + 4 <= end && t_lo == t_hi) {
                     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);      // never received: exactly zero
                     if ((any >> t_lo) & 1ull) {
-                        v = *(const float4*)(acc + e0);
+                        v = *(const float4*)((((hm >> (8 * t_lo)) & 1ull) ? acc1 : acc0) + e0);
                         v.x = scale_mean(v.x, inv_w, use_div, wf); v.y = scale_mean(v.y, inv_w, use_div, wf);
                         v.z = scale_mean(v.z, inv_w, use_div, wf); v.w = scale_mean(v.w, inv_w, use_div, wf);
                         dsum += (double)((v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w));
@@ -905,8 +929,9 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
                 } else {
                     for (u64 e = lo_e; e <= hi_e; ++e) {
                         float v = 0.f;
-                        if ((any >> div_small((u32)(e - elem0), g.P, inv_p)) & 1ull) {
-                            v = scale_mean(acc[e], inv_w, use_div, wf);
+                        const u32 t_e = div_small((u32)(e - elem0), g.P, inv_p);
+                        if ((any >> t_e) & 1ull) {
+                            v = scale_mean((((hm >> (8 * t_e)) & 1ull) ? acc1 : acc0)[e], inv_w, use_div, wf);
                             dsum += (double)(v * v);
                         }
                         out[e] = v;
@@ -921,6 +946,7 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
                 packet_span(g, seq, b, &elem, &len);
                 float s = 0.f;
                 if ((any >> t) & 1ull) {
+                    const float* acc = ((hm >> (8 * t)) & 1ull) ? acc1 : acc0;
                     for (u32 j = lane; j < len; j += WAVE) {
                         const float v = scale_mean(acc[elem + j], inv_w, use_div, wf);
                         out[elem + j] = v;
@@ -972,6 +998,48 @@ __global__ __launch_bounds__(256) void reduce_partials(const double* __restrict_
 }
 
 // ------------------------------------------------------------------------------------------
+// where to write: measuring a buffer against the accumulator copies
+// ------------------------------------------------------------------------------------------
+// On this chip a stream of payload reads with a few percent of result writes mixed in runs about
+// 15 % slower when the reads and the writes fall into the same third of the HBM address space
+// than when they fall into different thirds (measured with this very loop: 1.60 vs 1.39 ms per
+// 8.5 GB; which third a buffer lies in cannot be asked for, only measured).  The library
+// therefore keeps two copies of the accumulator in different thirds when it can, and sends the
+// spans a batch writes for the first time to the copy that is faster for that batch's buffer.
+//
+// The loop below has the access pattern of the gather (CLS_STREAMS streams of 1472-byte pieces,
+// each wave sums one piece per stream and stores the 1472-byte result): a plain linear copy does
+// not show the effect.  It reads CLS_SAMPLE_BYTES from src and writes CLS_SCRATCH_BYTES.
+#define CLS_STREAMS 32u
+#define CLS_PIECE 1472u
+#define CLS_SEQS 22795u
+#define CLS_SAMPLE_BYTES ((u64)CLS_STREAMS * CLS_SEQS * CLS_PIECE)      /* 1.07 GB */
+#define CLS_SCRATCH_BYTES ((u64)CLS_SEQS * CLS_PIECE)                    /* 33.6 MB */
+__global__ __launch_bounds__(256) void classify_rw(const uint8_t* __restrict__ src, float* __restrict__ scratch) {
+    const u32 lane = lane_id();
+    const u32 wave = (blockIdx.x * 256 + threadIdx.x) / WAVE, n_waves = gridDim.x * 4;
+    const bool second = lane < CLS_PIECE / 16 - WAVE;            // 92 units per piece: lanes 0..27 take two
+    for (u32 seq = wave; seq < CLS_SEQS; seq += n_waves) {
+        f4v a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0;
+        for (u32 w0 = 0; w0 < CLS_STREAMS; w0 += 4) {
+            f4v v0[4], v1[4];
+            #pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint8_t* b = src + ((u64)(w0 + j) * CLS_SEQS + seq) * CLS_PIECE + 16ull * lane;
+                v0[j] = __builtin_nontemporal_load((const f4v*)b);
+                v1[j] = f4v{0.f, 0.f, 0.f, 0.f};
+                if (second) v1[j] = __builtin_nontemporal_load((const f4v*)(b + 1024));
+            }
+            #pragma unroll
+            for (int j = 0; j < 4; ++j) { a0 += v0[j]; a1 += v1[j]; }
+        }
+        f4v* d = (f4v*)(scratch + (u64)seq * (CLS_PIECE / 4)) + lane;
+        *d = a0;
+        if (second) d[WAVE] = a1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
 struct dblp_ctx {
@@ -983,7 +1051,21 @@ struct dblp_ctx {
     int n_cus;
     // device state
     u32* d_first_seq; u64* d_b_off; u64* d_b_cnt;
-    u64* d_bitmap; u64* d_pending; float* d_acc; u64* d_counters;
+    u64* d_bitmap; u64* d_pending; u64* d_counters;
+    // accumulator: one or two copies (d_acc[1] == d_acc[0] when there is one); each copy's
+    // allocation ends with CLS_SCRATCH_BYTES that classify_rw may overwrite
+    void* acc_alloc[2]; float* d_acc[2]; float* d_scratch[2];
+    int n_acc;              // 1 or 2
+    int acc_distinct;       // the two copies were measured to lie in different thirds of HBM
+    float place_ms[2];      // that measurement: probe time writing to copy 0 / copy 1 (0 = not taken)
+    int place_steps;        // candidates tried by the placement search
+    int acc_policy;         // DBLP_ACC_*
+    int last_pick;          // copy the last batch wrote new spans to
+    u32 batch_no;
+    uint8_t* d_home;        // [n_pkts rounded up to 8] copy that holds each packet's span
+    struct Picked { const void* p; u64 bytes; int pick; } picked[32];   // measured buffers
+    u32 n_picked;
+    hipEvent_t cls_ev[2];
     u32* d_need; u32* d_missing; u64* d_offs; double* d_partials;
     u32* d_block_tallies;   // [IDX_BLOCKS_PER_CU * n_cus][5], written by index_arrivals
     u64* d_accept_rows;     // [2][ACCEPT_ROWS] accepted packets per gather block (staged grid, direct grid)
@@ -1060,15 +1142,118 @@ extern "C" int dblp_destroy(dblp_ctx* c) {
     if (!c) return DBLP_OK;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
-    void* dev[] = {c->d_first_seq, c->d_b_off, c->d_b_cnt, c->d_bitmap, c->d_pending, c->d_acc,
-                   c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials, c->d_block_tallies, c->d_accept_rows};
+    void* dev[] = {c->d_first_seq, c->d_b_off, c->d_b_cnt, c->d_bitmap, c->d_pending, c->acc_alloc[0], c->acc_alloc[1],
+                   c->d_home, c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials, c->d_block_tallies,
+                   c->d_accept_rows};
     for (void* p : dev) if (p) (void)hipFree(p);
+    for (hipEvent_t e : c->cls_ev) if (e) (void)hipEventDestroy(e);
     if (c->h_mailbox) (void)hipHostFree(c->h_mailbox);
     if (c->timed) { for (auto& t : *c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); } delete c->timed; }
     if (c->ev_pool) { for (auto e : *c->ev_pool) (void)hipEventDestroy(e); delete c->ev_pool; }
     free(c->h_first_seq); free(c->h_b_off); free(c->h_b_cnt);
     free(c);
     return DBLP_OK;
+}
+
+// Milliseconds of classify_rw reading src and writing scratch (best of two after one untimed run), < 0 on error.
+static float time_rw(dblp_ctx* c, const void* src, float* scratch) {
+    for (hipEvent_t& e : c->cls_ev)
+        if (!e && hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); e = nullptr; return -1.f; }
+    float best = -1.f;
+    for (int r = 0; r < 3; ++r) {
+        if (hipEventRecord(c->cls_ev[0], c->stream) != hipSuccess) return -1.f;
+        hipLaunchKernelGGL(classify_rw, dim3(4 * c->n_cus), dim3(256), 0, c->stream, (const uint8_t*)src, scratch);
+        if (hipEventRecord(c->cls_ev[1], c->stream) != hipSuccess) return -1.f;
+        if (hipEventSynchronize(c->cls_ev[1]) != hipSuccess) return -1.f;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->cls_ev[0], c->cls_ev[1]) != hipSuccess) return -1.f;
+        if (r > 0 && (best < 0.f || ms < best)) best = ms;
+    }
+    return best;
+}
+
+// (Re)allocates the accumulator as `copies` copies.  place != 0: search for a second copy in
+// another third of the HBM address space than the first, and have no second copy if none is found.
+// The contents of the round in progress are lost.
+#define PLACE_MAX_STEPS 24
+#define PLACE_STRIDE_BYTES (8ull << 30)
+static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, DBLP_EHIP, "accumulator_copies: synchronize");
+    for (int i = 0; i < 2; ++i) { if (c->acc_alloc[i]) (void)hipFree(c->acc_alloc[i]); c->acc_alloc[i] = nullptr; }
+    c->n_acc = 1; c->acc_distinct = 0; c->place_ms[0] = c->place_ms[1] = 0.f; c->place_steps = 0; c->n_picked = 0; c->last_pick = 0; c->round_open = 0; c->finalized = 0;
+    const size_t bytes = (c->N * sizeof(float) + 255) / 256 * 256;     // the scratch area starts aligned
+    const size_t scratch = copies == 2 ? CLS_SCRATCH_BYTES : 0;
+    if (hipMalloc(&c->acc_alloc[0], bytes + scratch) != hipSuccess) { (void)hipGetLastError(); return fail(c, DBLP_ENOMEM, "accumulator"); }
+    c->d_acc[0] = c->d_acc[1] = (float*)c->acc_alloc[0];
+    c->d_scratch[0] = c->d_scratch[1] = (float*)((uint8_t*)c->acc_alloc[0] + bytes);
+    if (copies != 2) return DBLP_OK;
+    auto adopt = [&](void* p) {
+        c->acc_alloc[1] = p; c->n_acc = 2;
+        c->d_acc[1] = (float*)p; c->d_scratch[1] = (float*)((uint8_t*)p + bytes);
+    };
+    if (!place) {
+        void* p = nullptr;
+        if (hipMalloc(&p, bytes + scratch) == hipSuccess) adopt(p); else (void)hipGetLastError();
+        return DBLP_OK;
+    }
+    // Walk through the free memory: candidate, then a holder allocation that pushes the next
+    // candidate further on, until a candidate measures differently from the first copy against
+    // the same read buffer (allocated next to the first copy) or half of the memory is held.
+    void* near0 = nullptr;
+    if (hipMalloc(&near0, CLS_SAMPLE_BYTES) != hipSuccess) { (void)hipGetLastError(); return DBLP_OK; }
+    size_t free_b = 0, total_b = 0;
+    if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); total_b = 0; }
+    const float t_ref = time_rw(c, near0, c->d_scratch[0]);
+    c->place_ms[0] = t_ref > 0.f ? t_ref : 0.f;
+    void* held[2 * PLACE_MAX_STEPS];
+    int n_held = 0;
+    size_t held_bytes = 0;
+    for (int step = 0; step < PLACE_MAX_STEPS && t_ref > 0.f && held_bytes < total_b / 2; ++step) {
+        void* cand = nullptr;
+        if (hipMalloc(&cand, bytes + scratch) != hipSuccess) { (void)hipGetLastError(); break; }
+        const float t = time_rw(c, near0, (float*)((uint8_t*)cand + bytes));
+        const float hi = t > t_ref ? t : t_ref, lo = t > t_ref ? t_ref : t;
+        c->place_ms[1] = t > 0.f ? t : 0.f;
+        c->place_steps = step + 1;
+        if (lo > 0.f && hi - lo > 0.05f * hi) { adopt(cand); c->acc_distinct = 1; break; }
+        held[n_held++] = cand; held_bytes += bytes + scratch;
+        void* holder = nullptr;
+        if (hipMalloc(&holder, PLACE_STRIDE_BYTES) != hipSuccess) { (void)hipGetLastError(); break; }
+        held[n_held++] = holder; held_bytes += PLACE_STRIDE_BYTES;
+    }
+    for (int i = 0; i < n_held; ++i) (void)hipFree(held[i]);
+    (void)hipFree(near0);
+    (void)hipGetLastError();
+    return DBLP_OK;
+}
+
+// Which copy the spans that this batch writes first should go to.
+static int pick_copy(dblp_ctx* c, const void* d_packets, u64 bytes, u64 n_slots, u64 n_arrivals) {
+    if (c->n_acc < 2) return 0;
+    switch (c->acc_policy) {
+    case DBLP_ACC_FIRST: return 0;
+    case DBLP_ACC_SECOND: return 1;
+    case DBLP_ACC_ALTERNATE: return (int)(c->batch_no & 1u);
+    default: break;
+    }
+    // automatic: measure the buffer once; small or thinly used buffers are not worth it
+    if (bytes < CLS_SAMPLE_BYTES || n_arrivals < n_slots / 8) return 0;
+    for (u32 i = 0; i < c->n_picked; ++i)
+        if (c->picked[i].p == d_packets && c->picked[i].bytes == bytes) return c->picked[i].pick;
+    const u64 last = (bytes - CLS_SAMPLE_BYTES) & ~15ull;
+    const u64 offs[3] = {0, (last / 2) & ~15ull, last};
+    const int n_offs = bytes >= 3 * CLS_SAMPLE_BYTES ? 3 : 1;
+    float t[2] = {0.f, 0.f};
+    for (int i = 0; i < n_offs; ++i)
+        for (int k = 0; k < 2; ++k) {
+            const float ms = time_rw(c, (const uint8_t*)d_packets + offs[i], c->d_scratch[k]);
+            if (ms < 0.f) { (void)hipGetLastError(); return 0; }
+            t[k] += ms;
+        }
+    const int pick = t[1] < 0.97f * t[0] ? 1 : 0;
+    dblp_ctx::Picked& slot = c->picked[c->n_picked < 32 ? c->n_picked++ : c->batch_no % 32];
+    slot.p = d_packets; slot.bytes = bytes; slot.pick = pick;
+    return pick;
 }
 
 #define FIN_BLOCKS_PER_CU 8
@@ -1138,7 +1323,7 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     ok = ok && hipMalloc(&c->d_b_cnt, B * sizeof(u64)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_bitmap, g.W * g.words_pw * sizeof(u64)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_pending, (u64)g.W * n_pkts * sizeof(u64)) == hipSuccess;
-    ok = ok && hipMalloc(&c->d_acc, c->N * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_home, (n_pkts + 7) / 8 * 8 + 8) == hipSuccess;
     ok = ok && hipMalloc(&c->d_counters, C_COUNT * sizeof(u64)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_need, pairs * sizeof(u32)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_missing, pairs * sizeof(u32)) == hipSuccess;
@@ -1164,6 +1349,11 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     hipLaunchKernelGGL(fill_u64, dim3(32), dim3(256), 0, c->stream, c->d_accept_rows, (u64)(2 * ACCEPT_ROWS), 0ull);
     e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess || hipGetLastError() != hipSuccess) { dblp_destroy(c); return DBLP_EHIP; }
+    // accumulator last: a second copy is worth its memory when one round moves enough bytes for a
+    // batch to be measured against the copies
+    const bool big = (u64)g.W * n_pkts * g.stride >= 2 * CLS_SAMPLE_BYTES;
+    const int rc = set_accumulator_copies(c, big ? 2 : 1, big ? 1 : 0);
+    if (rc != DBLP_OK) { dblp_destroy(c); return rc; }
     c->err[0] = 0;
     *out = c;
     return DBLP_OK;
@@ -1174,6 +1364,29 @@ extern "C" int dblp_layout(const dblp_ctx* c, uint64_t* n_pkts, uint32_t* stride
     if (n_pkts) *n_pkts = c->g.n_pkts;
     if (stride) *stride = c->g.stride;
     if (words_pw) *words_pw = c->g.words_pw;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_accumulator_copies(dblp_ctx* c, int copies, int place) {
+    if (!c) return DBLP_EINVAL;
+    if (copies != 1 && copies != 2) return fail(c, DBLP_EINVAL, "accumulator_copies: 1 or 2");
+    HIP_TRY(c, hipSetDevice(c->device));
+    return set_accumulator_copies(c, copies, place);
+}
+
+extern "C" int dblp_accumulator_policy(dblp_ctx* c, int policy) {
+    if (!c) return DBLP_EINVAL;
+    if (policy < DBLP_ACC_AUTO || policy > DBLP_ACC_ALTERNATE) return fail(c, DBLP_EINVAL, "accumulator_policy: unknown policy");
+    c->acc_policy = policy;
+    return DBLP_OK;
+}
+
+extern "C" int dblp_accumulator_info(const dblp_ctx* c, int* copies, int* distinct, int* last_pick, double* placement_ms) {
+    if (!c) return DBLP_EINVAL;
+    if (placement_ms) { placement_ms[0] = c->place_ms[0]; placement_ms[1] = c->place_ms[1]; placement_ms[2] = c->place_steps; }
+    if (copies) *copies = c->n_acc;
+    if (distinct) *distinct = c->acc_distinct;
+    if (last_pick) *last_pick = c->last_pick;
     return DBLP_OK;
 }
 
@@ -1271,6 +1484,9 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
                        const uint64_t* d_mask, const uint32_t* d_order, const uint64_t* d_queue, uint64_t n_arrivals) {
     HIP_TRY(c, hipSetDevice(c->device));
     const Geo& g = c->g;
+    const int pick = pick_copy(c, d_packets, n_slots * g.stride, n_slots, n_arrivals);
+    c->last_pick = pick;
+    ++c->batch_no;
     {
         ProfScope ps(c, DBLP_K_INDEX);
         const u32 grid = grid_for(c, (n_arrivals + 255) / 256, IDX_BLOCKS_PER_CU);
@@ -1297,20 +1513,20 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
             if (per_cu > GS_MAX_PER_CU) per_cu = GS_MAX_PER_CU;
             if (per_cu < 1) per_cu = 1;
-            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, const u64*, u64*, u32, u32, u32) =
+            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u64*, u64*, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
             hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, per_cu)), dim3((readers + 1) * WAVE),
-                               lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
-                               c->d_counters, c->d_accept_rows, sub, sub_log2, n_pass);
+                               lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
+                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows, sub, sub_log2, n_pass);
         }
         {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
             const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
             hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
-                               lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc,
-                               c->d_counters, c->d_accept_rows + ACCEPT_ROWS, sub >= 2 ? 1 : 0);
+                               lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
+                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows + ACCEPT_ROWS, sub >= 2 ? 1 : 0);
         }
     }
     LAUNCH_CHECK(c, "apply_arrivals");
@@ -1384,7 +1600,7 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
     const u32 grid = grid_for(c, (tiles + 3) / 4, FIN_BLOCKS_PER_CU);
     {
         ProfScope ps(c, DBLP_K_FINALIZE);
-        hipLaunchKernelGGL(finalize_mean, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc, d_out,
+        hipLaunchKernelGGL(finalize_mean, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc[0], c->d_acc[1], c->d_home, d_out,
                            1.0f / (float)W, !pow2, (float)W, c->d_partials);
     }
     LAUNCH_CHECK(c, "finalize");

@@ -20,15 +20,15 @@ def mk(W, sizes, P, loss=0.0, seed=7, place="shuffle", order="shuffle", name="t"
                        place, order, dict(kind="fixed", ppm=0), seed=seed)
 
 
-def both(sc, queue=False):
-    o, g = OracleRx(sc), GpuRx(sc, queue=queue)
+def both(sc, queue=False, **gpu_kw):
+    o, g = OracleRx(sc), GpuRx(sc, queue=queue, **gpu_kw)
     o.packetize_all()
     g.packetize_all()
     return o, g
 
 
-def run_both(sc, ppm, queue=False):
-    o, g = both(sc, queue)
+def run_both(sc, ppm, queue=False, **gpu_kw):
+    o, g = both(sc, queue, **gpu_kw)
     ref = run_iteration(o, sc, ppm)
     got = run_iteration(g, sc, ppm)
     return compare_results(got, ref, sc), got, ref
@@ -88,6 +88,73 @@ def test_parity_small_and_ragged_receive_queue(W, sizes, P, loss, ppm):
     """The same cases with every batch handed over as a receive queue of descriptors."""
     stats, got, ref = run_both(build_scenario(mk(W, sizes, P, loss)), ppm, queue=True)
     assert stats["rel_to_addends"] <= FLOAT_TOL
+
+
+# ------------------------------------------------------------------------------ two accumulator copies
+TWO_COPY_CASES = [CASES[i] for i in (3, 5, 6, 7, 10, 13, 14, 15)]
+
+
+@pytest.mark.parametrize("policy", [2, 3])      # always the second copy; alternate per batch
+@pytest.mark.parametrize("W,sizes,P,loss,ppm", TWO_COPY_CASES)
+def test_two_accumulator_copies_give_the_same_bits(W, sizes, P, loss, ppm, policy):
+    """Where a span lives must not show in any result: first transmissions and retransmission
+    rounds land in different copies under these policies."""
+    sc = build_scenario(mk(W, sizes, P, loss))
+    stats, got, ref = run_both(sc, ppm, acc_copies=2, acc_policy=policy)
+    assert stats["rel_to_addends"] <= FLOAT_TOL
+    g1 = GpuRx(sc); g1.packetize_all()
+    one = run_iteration(g1, sc, ppm)
+    assert np.array_equal(one["out"].view(np.uint32), got["out"].view(np.uint32))
+    assert one["norm"] == got["norm"] and one["counters"] == got["counters"]
+
+
+@pytest.mark.parametrize("queue", [False, True])
+def test_batches_alternate_between_accumulator_copies(queue):
+    """Four batches over the same spans, new spans going to alternating copies: every later batch
+    must find and update a span in the copy that holds it."""
+    sc = build_scenario(mk(5, [366 * 120 + 11, 3000, 1], 366, 0.1, place="shuffle", order="shuffle"))
+    L = sc.L
+    n = L.W * L.n_pkts
+    part = np.random.default_rng(11).integers(0, 4, size=n)
+    o, g = both(sc, queue, acc_copies=2, acc_policy=3)
+    assert g.agg.accumulator_info()["copies"] == 2
+    picks = []
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        for k in range(4):
+            rx.apply(0, n, sc.batches[0].mask, np.flatnonzero(part == k).astype(np.uint32))
+            if rx is g:
+                picks.append(g.agg.accumulator_info()["last_pick"])
+    assert picks == [0, 1, 0, 1]
+    assert np.array_equal(g.bitmap(), o.bitmap()) and g.counters() == o.counters()
+    from harness import abs_scale
+    ref, got = o.finalize(), g.finalize().astype(np.float64)
+    scale = abs_scale(sc, sc.survive0)
+    nz = scale > 0
+    assert (np.abs(got - ref)[nz] / scale[nz]).max() <= FLOAT_TOL and np.all(got[~nz] == 0)
+    assert g.phase_signal()[0] == pytest.approx(o.phase_signal()[0], rel=1e-6)
+
+
+def test_accumulator_api():
+    from paper_2605_01989_amd import DblpError, binding
+    sc = build_scenario(mk(2, [1000], 10))
+    g = GpuRx(sc)
+    info = g.agg.accumulator_info()
+    assert (info["copies"], info["distinct_thirds"], info["last_pick"]) == (1, False, 0)
+    g.begin_round(1)
+    g.agg.accumulator_copies(2)                           # discards the round in progress
+    with pytest.raises(DblpError) as e:
+        g.apply(0, 200, None, None)
+    assert e.value.code == binding.ESTATE
+    for bad in (0, 3):
+        with pytest.raises(DblpError) as e:
+            g.agg.accumulator_copies(bad)
+        assert e.value.code == binding.EINVAL
+    with pytest.raises(DblpError) as e:
+        g.agg.accumulator_policy(4)
+    assert e.value.code == binding.EINVAL
+    g.agg.accumulator_copies(1)
+    assert g.agg.accumulator_info()["copies"] == 1
 
 
 @pytest.mark.parametrize("queue", [False, True])
