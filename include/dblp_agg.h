@@ -110,7 +110,8 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
  *   synchronising the stream; the probe reads d_packets[0 .. n_slots * stride) and nothing
  *   else of the caller's) and remembers the answer for the last 32 buffers; smaller or thinly
  *   used buffers use the first copy.  FIRST / SECOND force a copy, ALTERNATE switches on
- *   every batch (for tests).
+ *   every batch (for tests).  Because AUTO waits for events on the stream, select FIRST or
+ *   SECOND before calling dblp_apply_arrivals* on a stream that is being captured.
  * dblp_accumulator_info: number of copies, whether they were measured to lie in different
  *   thirds, the copy the last batch wrote new spans to, and the placement measurement itself
  *   (placement_ms[0], [1]: probe time in ms writing to the first / second copy, 0 if not

@@ -13,7 +13,9 @@
 //                    worker order) into registers and writes the accumulator span once.
 // Every payload byte is read exactly once and the accumulator is written once per batch that
 // touches it; there are no floating-point atomics, so the sum is independent of the arrival
-// permutation.
+// permutation.  The accumulator may exist in two copies placed in different thirds of the HBM
+// address space (classify_rw measures which copy a packet buffer should be paired with); a
+// per-packet byte map records where each span lives.
 //
 // The probe (Sec. "Dynamically Changing Loss Tolerance"): loss_count (popcount of bitmap words +
 // DPP wave reduction), scan_need (exclusive prefix of the per-(worker,bucket) list lengths) and
@@ -1211,11 +1213,14 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
     for (int step = 0; step < PLACE_MAX_STEPS && t_ref > 0.f && held_bytes < total_b / 2; ++step) {
         void* cand = nullptr;
         if (hipMalloc(&cand, bytes + scratch) != hipSuccess) { (void)hipGetLastError(); break; }
-        const float t = time_rw(c, near0, (float*)((uint8_t*)cand + bytes));
-        const float hi = t > t_ref ? t : t_ref, lo = t > t_ref ? t_ref : t;
-        c->place_ms[1] = t > 0.f ? t : 0.f;
+        // both ends of the candidate must differ from the first copy, and in the same direction
+        // (a candidate that straddles two thirds is passed over); its contents are scratch here
+        const float t_end = time_rw(c, near0, (float*)((uint8_t*)cand + bytes));
+        const float t_beg = bytes >= CLS_SCRATCH_BYTES ? time_rw(c, near0, (float*)cand) : t_end;
+        auto differs = [&](float t) { const float hi = t > t_ref ? t : t_ref; return t > 0.f && fabsf(t - t_ref) > 0.05f * hi; };
+        c->place_ms[1] = t_end > 0.f ? t_end : 0.f;
         c->place_steps = step + 1;
-        if (lo > 0.f && hi - lo > 0.05f * hi) { adopt(cand); c->acc_distinct = 1; break; }
+        if (differs(t_end) && differs(t_beg) && (t_end < t_ref) == (t_beg < t_ref)) { adopt(cand); c->acc_distinct = 1; break; }
         held[n_held++] = cand; held_bytes += bytes + scratch;
         void* holder = nullptr;
         if (hipMalloc(&holder, PLACE_STRIDE_BYTES) != hipSuccess) { (void)hipGetLastError(); break; }
