@@ -104,7 +104,9 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
  *   against the first copy until one differs (temporarily holds up to half of the device
  *   memory; takes from 0.2 s on a fresh device to a few seconds); if none is found there is
  *   no second copy.  place == 0: plain second allocation, kept regardless.  Synchronises the stream; discards
- *   the round in progress (call dblp_begin_round again).  ENOMEM if not even one copy fits.
+ *   the round in progress (call dblp_begin_round again).  ENOMEM if not even one copy fits;
+ *   the context then has no accumulator and dblp_begin_round returns ESTATE until a later
+ *   dblp_accumulator_copies succeeds.
  * dblp_accumulator_policy: DBLP_ACC_AUTO (default) times a read+write probe kernel on the
  *   first batch seen from each packet buffer of at least 1 GiB (about 3 ms once per buffer,
  *   synchronising the stream; the probe reads d_packets[0 .. n_slots * stride) and nothing

@@ -1397,6 +1397,7 @@ extern "C" int dblp_accumulator_info(const dblp_ctx* c, int* copies, int* distin
 
 extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
     if (!c) return DBLP_EINVAL;
+    if (!c->acc_alloc[0]) return fail(c, DBLP_ESTATE, "begin_round: no accumulator (dblp_accumulator_copies ran out of memory)");
     HIP_TRY(c, hipSetDevice(c->device));
     const u64 n = c->g.W * c->g.words_pw;
     hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n + 255) / 256, 16)), dim3(256), 0, c->stream, c->d_bitmap, n, 0ull);
