@@ -68,6 +68,7 @@ __device__ __forceinline__ u32 dpp_u32(u32 identity, u32 v) {
 struct OpAdd { static __device__ __forceinline__ u32 id() { return 0u; } static __device__ __forceinline__ u32 f(u32 a, u32 b) { return a + b; } };
 struct OpMin { static __device__ __forceinline__ u32 id() { return 0xFFFFFFFFu; } static __device__ __forceinline__ u32 f(u32 a, u32 b) { return a < b ? a : b; } };
 struct OpMax { static __device__ __forceinline__ u32 id() { return 0u; } static __device__ __forceinline__ u32 f(u32 a, u32 b) { return a > b ? a : b; } };
+struct OpOr { static __device__ __forceinline__ u32 id() { return 0u; } static __device__ __forceinline__ u32 f(u32 a, u32 b) { return a | b; } };
 
 // Inclusive scan over the 64 lanes; all lanes must be active.  Lane 63 ends with the total.
 template <class Op>
@@ -598,8 +599,9 @@ template <int NP>
 __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_staged(
     Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
     float* acc0, float* acc1, uint8_t* __restrict__ home, u32 pick,
-    const u64* __restrict__ counters, u64* __restrict__ accept_rows, u32 sub, u32 sub_log2, u32 n_pass) {
-    extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, then slots
+    const u64* __restrict__ counters, u64* __restrict__ accept_rows, u32 sub, u32 sub_log2, u32 n_pass,
+    u32 table_in_lds) {
+    extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, slots, bucket table
     __shared__ u64 sh_elem[2][SUB];
     __shared__ u32 sh_len[2][SUB];
     __shared__ u32 sh_home[2][SUB];                 // accumulator copy each packet of the group goes to
@@ -617,6 +619,15 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
     float4* buf1 = sh_dyn + sub * upp;
     u32* sh_slot = (u32*)(sh_dyn + 2 * sub * upp);  // [W rounded up to a multiple of 64/sub][sub]
     const u32 wpl = WAVE >> sub_log2;               // workers per 64-lane load of the index
+    // bucket boundaries in LDS when the host made room for them: the span lookup of phase A is
+    // ten dependent loads, and every reader wave waits for it
+    const u32* fs = g.first_seq;
+    if (table_in_lds) {
+        u32* tab = sh_slot + (W + wpl - 1) / wpl * wpl * sub;
+        for (u32 i = threadIdx.x; i <= g.B; i += blockDim.x) tab[i] = g.first_seq[i];
+        fs = tab;
+        __syncthreads();
+    }
     const u32 s_lane = lane & (sub - 1), w_sub = lane >> sub_log2;
     const u32 submask = (1u << sub) - 1;
     const u32 grp0 = (u32)(lo >> sub_log2) + blockIdx.x;
@@ -657,10 +668,11 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                     accepted += (u32)__popcll(nb);
                 }
                 if (wave == n_readers - 1 && lane < sub && seq_l < g.n_pkts) {
-                    const u32 b = find_bucket(g.first_seq, g.B, seq_l);
-                    u64 elem; u32 len;
-                    packet_span(g, seq_l, b, &elem, &len);
-                    sh_elem[cur][lane] = elem; sh_len[cur][lane] = len;
+                    const u32 b = find_bucket(fs, g.B, seq_l);
+                    const u64 start = (u64)(seq_l - fs[b]) * g.P;
+                    const u64 left = g.b_cnt[b] - start;
+                    sh_elem[cur][lane] = g.b_off[b] + start;
+                    sh_len[cur][lane] = left < g.P ? (u32)left : g.P;
                 }
                 if (lane == 0) { sh_new[wave] = new_or; sh_old[wave] = old_or; }
             }
@@ -890,11 +902,19 @@ __device__ __forceinline__ float scale_mean(float v, float inv_w, int use_div, f
 // 16-byte aligned chunks (float4 load, scale, float4 store); chunks that straddle a packet or
 // the range's ends, and tiles that cross a bucket boundary, go element by element.
 // home[seq] (padded to a multiple of 8 entries) names the accumulator copy that holds the packet's span.
+template <bool TABLE_IN_LDS>
 __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restrict__ bitmap, const float* acc0,
                                                      const float* acc1, const uint8_t* __restrict__ home,
                                                      float* __restrict__ out, float inv_w, int use_div, float wf,
                                                      double* __restrict__ partials) {
     __shared__ double wsum[4];
+    extern __shared__ u32 fs_lds[];             // bucket boundaries (B + 1 words) when TABLE_IN_LDS
+    const u32* fs = g.first_seq;
+    if (TABLE_IN_LDS) {
+        for (u32 i = threadIdx.x; i <= g.B; i += blockDim.x) fs_lds[i] = g.first_seq[i];
+        __syncthreads();
+        fs = fs_lds;
+    }
     const u32 lane = lane_id();
     const u32 wave_in_block = threadIdx.x / WAVE;
     const u32 wave = blockIdx.x * (blockDim.x / WAVE) + wave_in_block;
@@ -905,13 +925,15 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
     for (u32 tile = wave; tile < n_tiles; tile += n_waves) {
         const u32 seq0 = tile * FIN_TILE;
         const u32 n_t = g.n_pkts - seq0 < FIN_TILE ? g.n_pkts - seq0 : FIN_TILE;
-        u64 any = 0;
-        for (u32 w = 0; w < g.W; ++w) any |= bitmap[(u64)w * g.words_pw + (seq0 >> 6)];
+        // OR of the workers' bitmap words: lane w loads worker w's word (one load instruction
+        // for the wave, W <= 64), the OR runs across the lanes
+        const u64 mine = lane < g.W ? bitmap[(u64)lane * g.words_pw + (seq0 >> 6)] : 0ull;
+        u64 any = ((u64)wave_reduce<OpOr>((u32)(mine >> 32)) << 32) | wave_reduce<OpOr>((u32)mine);
         any >>= (seq0 & 63);
         const u64 hm = *(const u64*)(home + seq0);          // byte t = copy of packet seq0 + t (valid where `any` has bit t)
-        u32 b = find_bucket(g.first_seq, g.B, seq0);
-        if (seq0 + n_t <= g.first_seq[b + 1]) {
-            const u64 elem0 = g.b_off[b] + (u64)(seq0 - g.first_seq[b]) * g.P;
+        u32 b = find_bucket(fs, g.B, seq0);
+        if (seq0 + n_t <= fs[b + 1]) {
+            const u64 elem0 = g.b_off[b] + (u64)(seq0 - fs[b]) * g.P;
             const u64 bucket_end = g.b_off[b] + g.b_cnt[b];
             const u64 end = elem0 + (u64)n_t * g.P < bucket_end ? elem0 + (u64)n_t * g.P : bucket_end;
             const u64 c1 = (end - 1) >> 2;
@@ -943,7 +965,7 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
         } else {
             for (u32 t = 0; t < n_t; ++t) {
                 const u32 seq = seq0 + t;
-                while (seq >= g.first_seq[b + 1]) ++b;
+                while (seq >= fs[b + 1]) ++b;
                 u64 elem; u32 len;
                 packet_span(g, seq, b, &elem, &len);
                 float s = 0.f;
@@ -1261,7 +1283,9 @@ static int pick_copy(dblp_ctx* c, const void* d_packets, u64 bytes, u64 n_slots,
     return pick;
 }
 
+#ifndef FIN_BLOCKS_PER_CU
 #define FIN_BLOCKS_PER_CU 8
+#endif
 #define ACCEPT_ROWS 8192   // >= blocks of any gather launch (n_cus * blocks per CU)
 #ifndef IDX_BLOCKS_PER_CU
 #define IDX_BLOCKS_PER_CU 8
@@ -1511,7 +1535,10 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
         while (sub >= 2 && 2u * sub * g.stride > GS_LDS_BUDGET) { sub >>= 1; --sub_log2; }
         if (sub >= 2) {   // two groups of packets fit in LDS: readers + writer wave
             const u32 wpl = WAVE / sub;
-            const size_t lds = 2ull * sub * g.stride + (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
+            size_t lds = 2ull * sub * g.stride + (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
+            const size_t table = ((size_t)g.B + 1) * sizeof(u32);
+            const u32 table_in_lds = table <= IDX_TABLE_LDS_MAX && lds + table <= 64u * 1024u ? 1u : 0u;   // a block's LDS limit
+            if (table_in_lds) lds += table;
             const u64 groups = ((u64)g.n_pkts + sub - 1) / sub;
             const u32 n_pass = (g.units + WAVE - 1) / WAVE;
             const u32 readers = sub < GS_READERS ? sub : GS_READERS;   // a reader wave takes whole packets
@@ -1519,13 +1546,14 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
             if (per_cu > GS_MAX_PER_CU) per_cu = GS_MAX_PER_CU;
             if (per_cu < 1) per_cu = 1;
-            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u64*, u64*, u32, u32, u32) =
+            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u64*, u64*, u32, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
             hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, per_cu)), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
-                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows, sub, sub_log2, n_pass);
+                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows, sub, sub_log2, n_pass,
+                               table_in_lds);
         }
         {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
@@ -1606,8 +1634,13 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
     const u32 grid = grid_for(c, (tiles + 3) / 4, FIN_BLOCKS_PER_CU);
     {
         ProfScope ps(c, DBLP_K_FINALIZE);
-        hipLaunchKernelGGL(finalize_mean, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc[0], c->d_acc[1], c->d_home, d_out,
-                           1.0f / (float)W, !pow2, (float)W, c->d_partials);
+        const size_t table = ((size_t)g.B + 1) * sizeof(u32);
+        if (table <= IDX_TABLE_LDS_MAX)
+            hipLaunchKernelGGL(finalize_mean<true>, dim3(grid), dim3(256), table, c->stream, g, c->d_bitmap, c->d_acc[0], c->d_acc[1],
+                               c->d_home, d_out, 1.0f / (float)W, !pow2, (float)W, c->d_partials);
+        else
+            hipLaunchKernelGGL(finalize_mean<false>, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc[0], c->d_acc[1],
+                               c->d_home, d_out, 1.0f / (float)W, !pow2, (float)W, c->d_partials);
     }
     LAUNCH_CHECK(c, "finalize");
     c->n_partials = grid;
