@@ -33,7 +33,7 @@ BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; late
 # keyed by the SHA-256 of the kernel source it was measured on; anything else reports null.
 # value = measured bytes / algorithmic bytes per launch on the default workload.
 PMC_TRAFFIC_RATIO: dict[str, float] = {
-    "11793635da822e9f19c76933a6baf55790ec928d72d50d7162e9251488efc651": 1.066,   # profiles/receiver_path_cfg5.md
+    "d9782f56966433270f9814fc02ca44281dc5d31818fdcfa4754cf0f6325b3a89": 1.067,   # profiles/receiver_path_cfg5.md
 }
 
 
