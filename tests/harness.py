@@ -166,6 +166,25 @@ def _dev(a: np.ndarray, as_dtype):
     return torch.from_numpy(np.ascontiguousarray(a).view(as_dtype)).cuda()
 
 
+def receive_queue(src: np.ndarray, n_slots: int, mask, order, n_arrivals=None) -> np.ndarray:
+    """The batch (per-slot worker table, survival mask, arrival order) as a receive queue: one
+    descriptor slot | worker << 32 per arrival that survived, in arrival order.  Arrivals whose
+    slot lies outside the buffer are kept (worker 0): the receiver must call them invalid."""
+    if order is None:
+        slots = np.arange(n_slots if n_arrivals is None else n_arrivals, dtype=np.uint64)
+    else:
+        slots = np.asarray(order, dtype=np.uint64)[:n_arrivals]
+    inside = slots < n_slots
+    keep = np.ones(slots.size, dtype=bool)
+    if mask is not None:
+        s_in = slots[inside]
+        words = np.asarray(mask, dtype=np.uint64)
+        keep[inside] = ((words[s_in >> np.uint64(6)] >> (s_in & np.uint64(63))) & np.uint64(1)).astype(bool)
+    worker = np.zeros(slots.size, dtype=np.uint64)
+    worker[inside] = np.asarray(src).astype(np.uint64)[slots[inside]]
+    return (slots | (worker << np.uint64(32)))[keep]
+
+
 class GpuRx:
     """Drives the HIP library on device-resident packets built by its own packetize."""
 
@@ -206,21 +225,8 @@ class GpuRx:
         self.agg.begin_round(rnd_id)
 
     def _descriptors(self, slot_base, n_slots, mask, order, n_arrivals):
-        """slot | worker << 32 per arrival that survived, in arrival order."""
-        if order is None:
-            slots = np.arange(n_slots if n_arrivals is None else n_arrivals, dtype=np.uint64)
-        else:
-            slots = np.asarray(order, dtype=np.uint64)[:n_arrivals]
-        inside = slots < n_slots
-        keep = np.ones(slots.size, dtype=bool)
-        if mask is not None:
-            s_in = slots[inside]
-            words = np.asarray(mask, dtype=np.uint64)
-            keep[inside] = ((words[s_in >> np.uint64(6)] >> (s_in & np.uint64(63))) & np.uint64(1)).astype(bool)
-        src = self.src[slot_base: slot_base + n_slots].cpu().numpy().view(np.uint16).astype(np.uint64)
-        worker = np.zeros(slots.size, dtype=np.uint64)
-        worker[inside] = src[slots[inside]]
-        return (slots | (worker << np.uint64(32)))[keep]
+        src = self.src[slot_base: slot_base + n_slots].cpu().numpy().view(np.uint16)
+        return receive_queue(src, n_slots, mask, order, n_arrivals)
 
     def apply(self, slot_base, n_slots, mask, order, n_arrivals=None):
         st = self.agg.stride

@@ -366,3 +366,46 @@ def test_epoch_controller_follows_the_server_algorithm():
     assert oracle.clr_trace(lo, hi, 3, crit).tolist() == want
     # one step per epoch degenerates to the per-iteration two-level rule
     assert oracle.clr_trace(lo, hi, 1, [1, 0, 1, 0]).tolist() == [lo, hi, lo, hi]
+
+
+# ------------------------------------------------------------------------------ receive-queue form
+def test_receive_queue_is_the_same_batch_to_the_oracle():
+    """The test harness turns (per-slot worker table, mask, order) into receive-queue descriptors
+    for the library's queue entry point.  The conversion is checked here on the CPU: feeding the
+    oracle the descriptors' slots as the order and the descriptors' workers as the worker table,
+    with no mask, must classify every arrival and produce every output exactly as the original
+    batch does -- duplicates, stale, out-of-range slots and foreign workers included."""
+    from harness import receive_queue
+    off, cnt = wl.buckets_from_sizes([40 * 7 + 3, 5, 64])
+    w = wl.Workload("q", wl.Layout(3, int(sum([40 * 7 + 3, 5, 64])), 7, off, cnt), 1e-3, dict(kind="bernoulli", p=0.2),
+                    "shuffle", "shuffle", dict(kind="fixed", ppm=0), seed=5)
+    sc = build_scenario(w)
+    L = sc.L
+    n = L.W * L.n_pkts
+    a = OracleRx(sc); a.packetize_all()
+    p = a.packets.reshape(-1, L.stride)
+    p[4, 4:6] = np.frombuffer(np.uint16(sc.rnd_id + 1).tobytes(), np.uint8)      # a stale packet
+    a.src[7] = 9                                                                 # a foreign worker
+    rng = np.random.default_rng(1)
+    order = np.concatenate([rng.permutation(n), rng.integers(0, n, 30), [n, n + 5]]).astype(np.uint32)   # duplicates, bad slots
+    mask = sc.batches[0].mask
+    a.begin_round(sc.rnd_id)
+    a.apply(0, n, mask, order)
+    q = receive_queue(a.src, n, mask, order, order.size)
+    assert q.size < order.size and np.all(q >> np.uint64(48) == 0)
+    b = OracleRx(sc); b.packets = a.packets
+    b.src = np.zeros(n, dtype=np.uint16)
+    slots = (q & np.uint64(0xFFFFFFFF)).astype(np.uint32)
+    inside = slots < n
+    # every slot has one worker in the table, so the queue's worker field is a function of the slot
+    b.src[slots[inside]] = (q[inside] >> np.uint64(32)).astype(np.uint16)
+    assert np.array_equal(b.src[np.unique(slots[inside])], a.src[np.unique(slots[inside])])
+    b.begin_round(sc.rnd_id)
+    b.apply(0, n, None, slots)
+    assert a.counters() == b.counters() and a.counters()["stale"] >= 1 and a.counters()["invalid"] >= 3
+    assert a.counters()["duplicate"] >= 1
+    assert np.array_equal(a.bitmap(), b.bitmap())
+    assert np.array_equal(a.finalize(), b.finalize())
+    ma, la, ca, _ = a.loss_account(0)
+    mb, lb, cb, _ = b.loss_account(0)
+    assert np.array_equal(ma, mb) and np.array_equal(la, lb) and ca == cb
