@@ -99,14 +99,18 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
  * dblp_finalize reads each span from its copy.  Results do not depend on any of this.
  *
  * dblp_create chooses two copies when one round carries at least 2 GiB of packets, else one.
- * dblp_accumulator_copies(copies = 1|2, place): reallocates.  place != 0: search for a second
+ * dblp_accumulator_copies(copies = 1|2, place): reallocates.  place = 1: search for a second
  *   copy in another third than the first: candidates are allocated 8 GiB apart and timed
  *   against the first copy until one differs (temporarily holds up to half of the device
- *   memory; takes from 0.2 s on a fresh device to a few seconds); if none is found there is
- *   no second copy.  place == 0: plain second allocation, kept regardless.  Synchronises the stream; discards
- *   the round in progress (call dblp_begin_round again).  ENOMEM if not even one copy fits;
- *   the context then has no accumulator and dblp_begin_round returns ESTATE until a later
- *   dblp_accumulator_copies succeeds.
+ *   memory; takes from 0.2 s on a fresh device to a few seconds).  If none is found, up to
+ *   three later attempts are made from dblp_apply_arrivals* under DBLP_ACC_AUTO: when a packet
+ *   buffer measures clearly slower against the first copy than another measurement did, one
+ *   fresh allocation is timed against that buffer and adopted if it is faster (this is the
+ *   only case in which those calls allocate).  place = 2: no search now, only the later
+ *   attempts.  place = 0: plain second allocation, kept regardless.  Synchronises the stream;
+ *   discards the round in progress (call dblp_begin_round again).  ENOMEM if not even one
+ *   copy fits; the context then has no accumulator and dblp_begin_round returns ESTATE until
+ *   a later dblp_accumulator_copies succeeds.
  * dblp_accumulator_policy: DBLP_ACC_AUTO (default) times a read+write probe kernel on the
  *   first batch seen from each packet buffer of at least 1 GiB (about 3 ms once per buffer,
  *   synchronising the stream; the probe reads d_packets[0 .. n_slots * stride) and nothing
@@ -117,7 +121,7 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
  * dblp_accumulator_info: number of copies, whether they were measured to lie in different
  *   thirds, the copy the last batch wrote new spans to, and the placement measurement itself
  *   (placement_ms[0], [1]: probe time in ms writing to the first / second copy, 0 if not
- *   taken; [2]: candidates the placement search tried).  Any pointer may be NULL. */
+ *   taken; [2]: candidates the placement search tried; [3]: later attempts made so far).  Any pointer may be NULL. */
 #define DBLP_ACC_AUTO 0
 #define DBLP_ACC_FIRST 1
 #define DBLP_ACC_SECOND 2
@@ -125,7 +129,7 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
 int dblp_accumulator_copies(dblp_ctx* ctx, int copies, int place);
 int dblp_accumulator_policy(dblp_ctx* ctx, int policy);
 int dblp_accumulator_info(const dblp_ctx* ctx, int* copies, int* distinct_thirds, int* last_pick,
-                          double placement_ms[3]);
+                          double placement_ms[4]);
 
 /* Alg. "DBLP_RECV", initialisation: empty bitmap, nothing received, counters zero; `round`
  * is the round counter that arriving packets must carry.  The accumulator is not cleared:

@@ -186,17 +186,19 @@ class Aggregator:
         self._check(lib().dblp_packetize_list(self._h, rnd & 0xFFFF, ptrs, _ptr(d_retx_list), n_entries, slot_base,
                                               n_slots, _ptr(d_packets), _ptr(d_src_worker)))
 
-    def accumulator_copies(self, copies: int, place: bool = False):
+    def accumulator_copies(self, copies: int, place: int = 0):
+        """place: 0 plain second allocation, 1 search for one in another third of HBM now (and later
+        if none is found), 2 only the later attempts against the caller's packet buffers."""
         self._check(lib().dblp_accumulator_copies(self._h, copies, int(place)))
 
     def accumulator_policy(self, policy: int):
         self._check(lib().dblp_accumulator_policy(self._h, policy))
 
     def accumulator_info(self) -> dict:
-        n, d, p, ms = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), (ctypes.c_double * 3)()
+        n, d, p, ms = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), (ctypes.c_double * 4)()
         self._check(lib().dblp_accumulator_info(self._h, ctypes.byref(n), ctypes.byref(d), ctypes.byref(p), ms))
         return dict(copies=n.value, distinct_thirds=bool(d.value), last_pick=p.value,
-                    placement_ms=[round(ms[0], 4), round(ms[1], 4)], placement_steps=int(ms[2]))
+                    placement_ms=[round(ms[0], 4), round(ms[1], 4)], placement_steps=int(ms[2]), late_attempts=int(ms[3]))
 
     def apply_arrivals(self, d_packets, d_src_worker, n_slots, d_mask_words=None, d_order=None, n_arrivals=None):
         if n_arrivals is None:

@@ -1066,6 +1066,7 @@ __global__ __launch_bounds__(256) void classify_rw(const uint8_t* __restrict__ s
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
+#define DBLP_LATE_TRIES 3      // attempts to find a second accumulator copy after set-up
 struct dblp_ctx {
     Geo g;
     u64 N;
@@ -1083,6 +1084,11 @@ struct dblp_ctx {
     int acc_distinct;       // the two copies were measured to lie in different thirds of HBM
     float place_ms[2];      // that measurement: probe time writing to copy 0 / copy 1 (0 = not taken)
     int place_steps;        // candidates tried by the placement search
+    int want_second;        // a second copy was asked for with placement and not found
+    int late_left;          // attempts left to find it later, against a caller's buffer
+    int late_used;          // attempts made
+    float t_min;            // fastest probe time per sample seen so far against the first copy
+    void* late_held[2 * DBLP_LATE_TRIES]; int n_late_held;   // rejected late candidates, kept while attempts remain
     int acc_policy;         // DBLP_ACC_*
     int last_pick;          // copy the last batch wrote new spans to
     u32 batch_no;
@@ -1108,6 +1114,11 @@ struct dblp_ctx {
     std::vector<hipEvent_t>* ev_pool; // free events
     char err[256];
 };
+
+static void release_late_held(dblp_ctx* c) {
+    for (int i = 0; i < c->n_late_held; ++i) (void)hipFree(c->late_held[i]);
+    c->n_late_held = 0;
+}
 
 static hipEvent_t prof_event(dblp_ctx* c) {
     hipEvent_t e = nullptr;
@@ -1170,6 +1181,7 @@ extern "C" int dblp_destroy(dblp_ctx* c) {
                    c->d_home, c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials, c->d_block_tallies,
                    c->d_accept_rows};
     for (void* p : dev) if (p) (void)hipFree(p);
+    release_late_held(c);
     for (hipEvent_t e : c->cls_ev) if (e) (void)hipEventDestroy(e);
     if (c->h_mailbox) (void)hipHostFree(c->h_mailbox);
     if (c->timed) { for (auto& t : *c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); } delete c->timed; }
@@ -1204,7 +1216,9 @@ static float time_rw(dblp_ctx* c, const void* src, float* scratch) {
 static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, DBLP_EHIP, "accumulator_copies: synchronize");
     for (int i = 0; i < 2; ++i) { if (c->acc_alloc[i]) (void)hipFree(c->acc_alloc[i]); c->acc_alloc[i] = nullptr; }
-    c->n_acc = 1; c->acc_distinct = 0; c->place_ms[0] = c->place_ms[1] = 0.f; c->place_steps = 0; c->n_picked = 0; c->last_pick = 0; c->round_open = 0; c->finalized = 0;
+    release_late_held(c);
+    c->n_acc = 1; c->acc_distinct = 0; c->place_ms[0] = c->place_ms[1] = 0.f; c->place_steps = 0;
+    c->want_second = 0; c->late_left = 0; c->late_used = 0; c->t_min = 0.f; c->n_picked = 0; c->last_pick = 0; c->round_open = 0; c->finalized = 0;
     const size_t bytes = (c->N * sizeof(float) + 255) / 256 * 256;     // the scratch area starts aligned
     const size_t scratch = copies == 2 ? CLS_SCRATCH_BYTES : 0;
     if (hipMalloc(&c->acc_alloc[0], bytes + scratch) != hipSuccess) { (void)hipGetLastError(); return fail(c, DBLP_ENOMEM, "accumulator"); }
@@ -1220,15 +1234,23 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
         if (hipMalloc(&p, bytes + scratch) == hipSuccess) adopt(p); else (void)hipGetLastError();
         return DBLP_OK;
     }
+    if (place == 2) {        // no search now: only the later attempts against the caller's buffers
+        c->want_second = 1; c->late_left = DBLP_LATE_TRIES;
+        return DBLP_OK;
+    }
     // Walk through the free memory: candidate, then a holder allocation that pushes the next
     // candidate further on, until a candidate measures differently from the first copy against
-    // the same read buffer (allocated next to the first copy) or half of the memory is held.
+    // the same read buffer or half of the memory is held.
+    // what the probe reads: a buffer allocated right after the first copy (next to its end, where
+    // the scratch area that the reference measurement writes lies)
     void* near0 = nullptr;
     if (hipMalloc(&near0, CLS_SAMPLE_BYTES) != hipSuccess) { (void)hipGetLastError(); return DBLP_OK; }
+    const void* rd = near0;
     size_t free_b = 0, total_b = 0;
     if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); total_b = 0; }
-    const float t_ref = time_rw(c, near0, c->d_scratch[0]);
+    const float t_ref = time_rw(c, rd, c->d_scratch[0]);
     c->place_ms[0] = t_ref > 0.f ? t_ref : 0.f;
+    float t_fastest = t_ref > 0.f ? t_ref : 0.f;          // of the probe times seen in this search
     void* held[2 * PLACE_MAX_STEPS];
     int n_held = 0;
     size_t held_bytes = 0;
@@ -1237,11 +1259,12 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
         if (hipMalloc(&cand, bytes + scratch) != hipSuccess) { (void)hipGetLastError(); break; }
         // both ends of the candidate must differ from the first copy, and in the same direction
         // (a candidate that straddles two thirds is passed over); its contents are scratch here
-        const float t_end = time_rw(c, near0, (float*)((uint8_t*)cand + bytes));
-        const float t_beg = bytes >= CLS_SCRATCH_BYTES ? time_rw(c, near0, (float*)cand) : t_end;
+        const float t_end = time_rw(c, rd, (float*)((uint8_t*)cand + bytes));
+        const float t_beg = bytes >= CLS_SCRATCH_BYTES ? time_rw(c, rd, (float*)cand) : t_end;
         auto differs = [&](float t) { const float hi = t > t_ref ? t : t_ref; return t > 0.f && fabsf(t - t_ref) > 0.05f * hi; };
         c->place_ms[1] = t_end > 0.f ? t_end : 0.f;
         c->place_steps = step + 1;
+        if (t_end > 0.f && t_end < t_fastest) t_fastest = t_end;
         if (differs(t_end) && differs(t_beg) && (t_end < t_ref) == (t_beg < t_ref)) { adopt(cand); c->acc_distinct = 1; break; }
         held[n_held++] = cand; held_bytes += bytes + scratch;
         void* holder = nullptr;
@@ -1249,18 +1272,19 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
         held[n_held++] = holder; held_bytes += PLACE_STRIDE_BYTES;
     }
     for (int i = 0; i < n_held; ++i) (void)hipFree(held[i]);
-    (void)hipFree(near0);
+    if (near0) (void)hipFree(near0);
+    if (c->n_acc < 2) { c->want_second = 1; c->late_left = DBLP_LATE_TRIES; c->t_min = t_fastest; }
     (void)hipGetLastError();
     return DBLP_OK;
 }
 
 // Which copy the spans that this batch writes first should go to.
 static int pick_copy(dblp_ctx* c, const void* d_packets, u64 bytes, u64 n_slots, u64 n_arrivals) {
-    if (c->n_acc < 2) return 0;
+    if (c->n_acc < 2 && !(c->want_second && c->late_left > 0)) return 0;
     switch (c->acc_policy) {
     case DBLP_ACC_FIRST: return 0;
-    case DBLP_ACC_SECOND: return 1;
-    case DBLP_ACC_ALTERNATE: return (int)(c->batch_no & 1u);
+    case DBLP_ACC_SECOND: return c->n_acc == 2 ? 1 : 0;
+    case DBLP_ACC_ALTERNATE: return c->n_acc == 2 ? (int)(c->batch_no & 1u) : 0;
     default: break;
     }
     // automatic: measure the buffer once; small or thinly used buffers are not worth it
@@ -1270,14 +1294,54 @@ static int pick_copy(dblp_ctx* c, const void* d_packets, u64 bytes, u64 n_slots,
     const u64 last = (bytes - CLS_SAMPLE_BYTES) & ~15ull;
     const u64 offs[3] = {0, (last / 2) & ~15ull, last};
     const int n_offs = bytes >= 3 * CLS_SAMPLE_BYTES ? 3 : 1;
-    float t[2] = {0.f, 0.f};
-    for (int i = 0; i < n_offs; ++i)
-        for (int k = 0; k < 2; ++k) {
-            const float ms = time_rw(c, (const uint8_t*)d_packets + offs[i], c->d_scratch[k]);
-            if (ms < 0.f) { (void)hipGetLastError(); return 0; }
-            t[k] += ms;
+    auto measure = [&](float* scratch) {           // summed over the sample positions, < 0 on error
+        float sum = 0.f;
+        for (int i = 0; i < n_offs; ++i) {
+            const float ms = time_rw(c, (const uint8_t*)d_packets + offs[i], scratch);
+            if (ms < 0.f) { (void)hipGetLastError(); return -1.f; }
+            sum += ms;
         }
-    const int pick = t[1] < 0.97f * t[0] ? 1 : 0;
+        return sum;
+    };
+    const float t0 = measure(c->d_scratch[0]);
+    if (t0 < 0.f) return 0;
+    int pick = 0;
+    if (c->n_acc == 2) {
+        const float t1 = measure(c->d_scratch[1]);
+        pick = t1 > 0.f && t1 < 0.97f * t0 ? 1 : 0;
+    } else {
+        // No second copy yet (the search at set-up found none).  This buffer is clearly slower
+        // against the first copy than some other measurement was: try once more, now that the
+        // caller's buffers occupy the memory, with a fresh allocation measured against this very
+        // buffer at both of its ends.  At most DBLP_LATE_TRIES such attempts per set-up.
+        const float per_sample = t0 / (float)n_offs;
+        if (c->t_min <= 0.f || per_sample < c->t_min) c->t_min = per_sample;
+        if (per_sample > 1.06f * c->t_min) {
+            --c->late_left; ++c->late_used;
+            const size_t acc_bytes = (c->N * sizeof(float) + 255) / 256 * 256;
+            void* cand = nullptr;
+            if (hipMalloc(&cand, acc_bytes + CLS_SCRATCH_BYTES) == hipSuccess) {
+                const float t_end = measure((float*)((uint8_t*)cand + acc_bytes));
+                const float t_beg = acc_bytes >= CLS_SCRATCH_BYTES ? measure((float*)cand) : t_end;
+                if (t_end > 0.f && t_beg > 0.f && t_end < 0.95f * t0 && t_beg < 0.95f * t0) {
+                    c->acc_alloc[1] = cand; c->n_acc = 2; c->acc_distinct = 1; c->want_second = 0;
+                    c->d_acc[1] = (float*)cand; c->d_scratch[1] = (float*)((uint8_t*)cand + acc_bytes);
+                    c->n_picked = 0;                      // earlier answers were given without a second copy
+                    pick = 1;
+                } else {
+                    // keep it (and a holder behind it) until the attempts are over, so that the
+                    // next attempt gets memory from somewhere else
+                    c->late_held[c->n_late_held++] = cand;
+                    void* holder = nullptr;
+                    if (hipMalloc(&holder, PLACE_STRIDE_BYTES) == hipSuccess) c->late_held[c->n_late_held++] = holder;
+                    else (void)hipGetLastError();
+                }
+            } else {
+                (void)hipGetLastError();
+            }
+            if (c->n_acc == 2 || c->late_left == 0) release_late_held(c);
+        }
+    }
     dblp_ctx::Picked& slot = c->picked[c->n_picked < 32 ? c->n_picked++ : c->batch_no % 32];
     slot.p = d_packets; slot.bytes = bytes; slot.pick = pick;
     return pick;
@@ -1399,6 +1463,7 @@ extern "C" int dblp_layout(const dblp_ctx* c, uint64_t* n_pkts, uint32_t* stride
 extern "C" int dblp_accumulator_copies(dblp_ctx* c, int copies, int place) {
     if (!c) return DBLP_EINVAL;
     if (copies != 1 && copies != 2) return fail(c, DBLP_EINVAL, "accumulator_copies: 1 or 2");
+    if (place < 0 || place > 2) return fail(c, DBLP_EINVAL, "accumulator_copies: place is 0, 1 or 2");
     HIP_TRY(c, hipSetDevice(c->device));
     return set_accumulator_copies(c, copies, place);
 }
@@ -1412,7 +1477,7 @@ extern "C" int dblp_accumulator_policy(dblp_ctx* c, int policy) {
 
 extern "C" int dblp_accumulator_info(const dblp_ctx* c, int* copies, int* distinct, int* last_pick, double* placement_ms) {
     if (!c) return DBLP_EINVAL;
-    if (placement_ms) { placement_ms[0] = c->place_ms[0]; placement_ms[1] = c->place_ms[1]; placement_ms[2] = c->place_steps; }
+    if (placement_ms) { placement_ms[0] = c->place_ms[0]; placement_ms[1] = c->place_ms[1]; placement_ms[2] = c->place_steps; placement_ms[3] = c->late_used; }
     if (copies) *copies = c->n_acc;
     if (distinct) *distinct = c->acc_distinct;
     if (last_pick) *last_pick = c->last_pick;
@@ -1422,6 +1487,7 @@ extern "C" int dblp_accumulator_info(const dblp_ctx* c, int* copies, int* distin
 extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
     if (!c) return DBLP_EINVAL;
     if (!c->acc_alloc[0]) return fail(c, DBLP_ESTATE, "begin_round: no accumulator (dblp_accumulator_copies ran out of memory)");
+    if (c->n_late_held) { HIP_TRY(c, hipStreamSynchronize(c->stream)); release_late_held(c); }   // not kept across rounds
     HIP_TRY(c, hipSetDevice(c->device));
     const u64 n = c->g.W * c->g.words_pw;
     hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n + 255) / 256, 16)), dim3(256), 0, c->stream, c->d_bitmap, n, 0ull);
