@@ -1,8 +1,9 @@
-"""Parity at full size, in the configuration bench.py times: the 1.3B-element, W=32 workload with
+"""Parity at full size, in the configurations bench.py times: the 1.3B-element, W=32 workload with
 every packet of a round resident in HBM (167 GB), chunk-streamed application, shuffled placement
-and arrival order, burst loss, a 2 % bound with retransmission rounds.
+and arrival order, burst loss, a 2 % bound with retransmission rounds; and the 124M-element (W=8)
+and 355M-element (W=16, 4 KB packets, microburst windows) workloads, each applied as one batch.
 
-The oracle cannot run 113.7 M packets' payloads in seconds, so it computes sampled outputs one by
+The oracle cannot run a whole round's payloads in seconds, so it computes sampled outputs one by
 one: for a sample of buckets it is given exactly that bucket's packets, in their original relative
 arrival order, and must reproduce the GPU's per-(worker, bucket) counts, retransmit-list entries,
 bitmap bits and aggregated elements for that bucket (loss accounting and aggregation are
@@ -17,8 +18,6 @@ import pytest
 import workloads as wl
 
 pytestmark = pytest.mark.gpu
-
-BOUND_PPM = 20_000
 
 
 _SURVIVE = {}
@@ -92,10 +91,16 @@ def bucket_subproblem(job, b, probes, bound_ppm):
     return rec, rel
 
 
-def test_cfg5_full_size_sampled_buckets_and_global_properties():
+# workload, bound of the iteration (cfg3: the tight level of its three-level policy; cfg4: its fixed
+# bound; cfg5: 2 %), buckets always sampled besides the first two, the last two and seven random ones
+FULL_SIZE = [("cfg3", 10_000, ()), ("cfg4", 80_000, ()), ("cfg5", 20_000, (43, 44))]
+
+
+@pytest.mark.parametrize("name,BOUND_PPM,extra", FULL_SIZE)
+def test_full_size_sampled_buckets_and_global_properties(name, BOUND_PPM, extra):
     import torch
     import bench
-    w = wl.workload("cfg5")
+    w = wl.workload(name)
     job = bench.DeviceJob(w, n_masks=1)
     L = job.L
     probes = []
@@ -122,7 +127,7 @@ def test_cfg5_full_size_sampled_buckets_and_global_properties():
     job.agg.get_bitmap(bitmap)
     words = bitmap.cpu().numpy().view(np.uint64).reshape(L.W, job.agg.words_pw)
     rng = np.random.default_rng(2605)
-    sample = sorted({0, 43, 44, L.B - 2, L.B - 1, *rng.integers(1, L.B - 2, size=7).tolist()})
+    sample = sorted({0, 1, *extra, L.B - 2, L.B - 1, *rng.integers(1, L.B - 2, size=7).tolist()})
     worst = 0.0
     for b in sample:
         rec, rel = bucket_subproblem(job, b, probes, BOUND_PPM)
@@ -131,7 +136,7 @@ def test_cfg5_full_size_sampled_buckets_and_global_properties():
         gbits = (words[:, seqs >> 6] >> (seqs & 63).astype(np.uint64)) & np.uint64(1)
         assert np.array_equal(gbits.astype(np.uint8), rec), f"bucket {b}: bitmap differs"
         worst = max(worst, rel)
-    print(f"cfg5 full size: rounds={res['rounds']} first list={first['count']} accepted={counters['accepted']} "
+    print(f"{name} full size: accumulator={job.agg.accumulator_info()} rounds={res['rounds']} first list={first['count']} accepted={counters['accepted']} "
           f"sampled buckets={sample} worst float rel={worst:.2e}")
     # --- the other hand-over form (mask + order + per-slot worker table instead of receive queues)
     # must give the same bits: the sum over workers is formed in worker order either way
@@ -139,7 +144,8 @@ def test_cfg5_full_size_sampled_buckets_and_global_properties():
     job.queue = False
     job.masks = [job._mask_for(0)]
     res2 = job.step(0, BOUND_PPM)
-    assert job.agg.get_counters() == counters and res2["rounds"] == res["rounds"] and res2["norm"] == res["norm"]
+    assert job.agg.get_counters() == counters and res2["rounds"] == res["rounds"]
+    assert res2["norm"] == pytest.approx(res["norm"], rel=1e-12)     # spans may live in other copies this time
     bitmap2 = torch.empty_like(bitmap)
     job.agg.get_bitmap(bitmap2)
     assert torch.equal(bitmap, bitmap2)
