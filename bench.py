@@ -259,7 +259,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, "
                          "to scale rocprofv3's FETCH_SIZE / WRITE_SIZE readings)")
-    ap.add_argument("--cpu-sample-elems", type=int, default=96_000_000)
+    ap.add_argument("--cpu-sample-bytes", type=float, default=24e9,
+                    help="packet bytes of the sample the CPU oracle is timed on (the workload scaled down "
+                         "to that many bytes of first transmissions; about 10 s of single-threaded work)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (all workers are simulated in that GPU's "
@@ -358,7 +360,7 @@ def main():
     if not args.no_cpu_baseline:
         del job
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems)
+        out["cpu_baseline"] = cpu_baseline(w, max(1_000_000, int(args.cpu_sample_bytes / (4 * L.W))))
     print(json.dumps(out), flush=True)
 
 
