@@ -21,7 +21,10 @@
  *   - All work is enqueued on the hipStream_t given at creation (passed as
  *     void*).  Calls are asynchronous except those that return host scalars
  *     (dblp_loss_account, dblp_phase_signal, dblp_get_counters,
- *     dblp_packetize), which synchronise that stream.
+ *     dblp_packetize), which synchronise that stream; dblp_accumulator_copies
+ *     does too, and so does dblp_apply_arrivals* the first time it sees a
+ *     packet buffer of 1 GiB or more while the accumulator policy is AUTO
+ *     (see "The accumulator and where it lives").
  *   - A context is not thread-safe; use one per host thread.
  *
  * Geometry.  The gradient has N fp32 elements, tiled in order by B buckets
@@ -37,7 +40,8 @@
  *     uint32 seq; uint16 round; uint16 len_floats; float payload[len_floats]; zero padding
  * With P = 366 the stride is 1472 bytes, the UDP payload of a 1500-byte MTU.
  * The worker a packet came from is not in the header (the paper identifies it
- * by the UDP port): it is given per slot in d_src_worker.
+ * by the UDP port): it is given per slot in d_src_worker, or per arrival in the
+ * descriptors of a receive queue (dblp_apply_arrivals_queue).
  */
 #ifndef DBLP_AGG_H
 #define DBLP_AGG_H
@@ -78,8 +82,11 @@ typedef struct {
 } dblp_config;
 
 /* Allocates the context and its device state (bitmap W x ceil(n_pkts/64) words, arrival
- * index W x n_pkts x 8 bytes, accumulator N floats, per-bucket counters).  *out is set only
- * on success.  Errors: EINVAL (bad table, W too large, n_pkts >= 2^32), ENOMEM, EHIP. */
+ * index W x n_pkts x 8 bytes, accumulator N floats in one or two copies, one byte per packet
+ * sequence number, per-bucket counters).  For workloads of 2 GiB per round or more it also
+ * searches for the second accumulator copy (see below), which takes 0.2 s to a few seconds.
+ * *out is set only on success.  Errors: EINVAL (bad table, W too large, n_pkts >= 2^32),
+ * ENOMEM, EHIP. */
 int dblp_create(dblp_ctx** out, const dblp_config* cfg);
 
 /* Frees everything the context owns.  NULL is accepted. */
