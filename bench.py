@@ -91,9 +91,14 @@ class DeviceJob:
         self.masks = [self._mask_for(it) for it in range(n_masks)]
         self.d_survive = {}
         self.per_iteration_retx = per_iteration_retx
+        self.d_survive_words = {}    # the same per slot, as mask words over the whole buffer
         for r in range(1, 0 if per_iteration_retx else drawn_rounds + 1):
             s = w.survive(0, r, self.slot_of)
             self.d_survive[r] = torch.from_numpy(s.reshape(-1)).to(dev)
+            by_slot = torch.zeros(self.n_slots, dtype=torch.uint8, device=dev)
+            by_slot[self.d_slot_of.long()] = self.d_survive[r]
+            self.d_survive_words[r] = self._pack_bits(by_slot)
+            del by_slot
         torch.cuda.synchronize()
         log(f"[bench] masks ready {time.time() - t0:.1f}s")
 
@@ -187,11 +192,19 @@ class DeviceJob:
             if self.per_iteration_retx and rounds <= self.w.drawn_rounds:
                 d_s = torch.from_numpy(self.w.survive(it, rounds, self.slot_of).reshape(-1)).cuda()
                 idx = idx[d_s[idx].bool()]
-            elif rounds in self.d_survive:
-                idx = idx[self.d_survive[rounds][idx].bool()]
-            slots = self.d_slot_of[idx]
-            resent += int(slots.numel())
-            agg.apply_arrivals(self.packets, self.src, self.n_slots, None, slots, slots.numel())
+                slots = self.d_slot_of[idx]
+                resent += int(slots.numel())
+                agg.apply_arrivals(self.packets, self.src, self.n_slots, None, slots, slots.numel())
+            else:
+                # every listed packet is sent again; the ones this round's loss draw takes are masked
+                # out (lost on the wire: never looked at).  No host round trip besides the probe's.
+                slots = self.d_slot_of[idx]
+                words = self.d_survive_words.get(rounds)
+                agg.apply_arrivals(self.packets, self.src, self.n_slots, words, slots, count)
+                if words is not None:
+                    resent = None          # survivors not counted here: the caller derives them from the accepted counter
+                elif resent is not None:
+                    resent += count        # a round without drawn loss: everything arrives
         agg.finalize(self.d_out)
         prev = agg.get_prev_norm()
         if prev is not None:
@@ -295,7 +308,7 @@ def main():
     bound = first_bound(w)
     for t in range(args.warmup):
         r = job.step(t, bound, ratio(t))
-        log(f"[bench] warmup {t}: bound={bound} rounds={r['rounds']} resent={r['resent']} delta={r['rel_delta']:.4f}")
+        log(f"[bench] warmup {t}: bound={bound} rounds={r['rounds']} delta={r['rel_delta']:.4f}")
         bound = next_bound(w, r["rel_delta"], r["critical"])
     agg.profile_enable(True)
     for k in range(binding.K_FINALIZE + 1):
@@ -311,9 +324,11 @@ def main():
         r = job.step(t, bound, ratio(t))
         c = agg.get_counters()
         accepted_total += c["accepted"]
-        resent_total += r["resent"]
+        # packets that arrived in retransmission rounds = accepted - first-transmission survivors
+        resent = r["resent"] if r["resent"] is not None else c["accepted"] - (job.n_slots - r["lost_first"])
+        resent_total += resent
         rounds_total += r["rounds"]
-        per_step.append(dict(bound_ppm=bound, rounds=r["rounds"], resent=r["resent"], accepted=c["accepted"]))
+        per_step.append(dict(bound_ppm=bound, rounds=r["rounds"], resent=resent, accepted=c["accepted"]))
         bound = next_bound(w, r["rel_delta"], r["critical"])
     ev1.record()
     torch.cuda.synchronize()
