@@ -188,7 +188,8 @@ def receive_queue(src: np.ndarray, n_slots: int, mask, order, n_arrivals=None) -
 class GpuRx:
     """Drives the HIP library on device-resident packets built by its own packetize."""
 
-    def __init__(self, sc: Scenario, eta: float = 0.5, queue: bool = False, acc_copies: int = 1, acc_policy: int = 0):
+    def __init__(self, sc: Scenario, eta: float = 0.5, queue: bool = False, acc_copies: int = 1, acc_policy: int = 0,
+                 acc_place: int = 0):
         """queue=True hands every batch over as a receive queue (dblp_apply_arrivals_queue): the
         descriptors are built here, on the host, from the same (mask, order, per-slot worker)."""
         import torch
@@ -198,7 +199,7 @@ class GpuRx:
         self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, eta)
         assert (self.agg.n_pkts, self.agg.stride) == (L.n_pkts, L.stride)
         if acc_copies == 2:      # a plain second accumulator copy, and which copy batches write new spans to
-            self.agg.accumulator_copies(2, place=False)
+            self.agg.accumulator_copies(2, place=acc_place)
             self.agg.accumulator_policy(acc_policy)
         n_slots = L.W * L.n_pkts
         self.packets = torch.zeros(n_slots * L.stride, dtype=torch.uint8, device="cuda")

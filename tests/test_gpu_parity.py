@@ -135,6 +135,28 @@ def test_batches_alternate_between_accumulator_copies(queue):
     assert g.phase_signal()[0] == pytest.approx(o.phase_signal()[0], rel=1e-6)
 
 
+@pytest.mark.parametrize("place", [0, 2])
+def test_automatic_copy_choice_on_a_buffer_large_enough_to_be_measured(place):
+    """1.3 GB of packets: under the automatic policy the library times its probe kernel on the
+    buffer before the first batch (place 0: against two plain copies; place 2: against the one
+    copy it has, possibly adopting a second one it allocates then).  Whatever it decides, the
+    bits are those of a one-copy run."""
+    sc = build_scenario(mk(8, [20_000_000, 15_000_000, 5_000_007], 366, 0.03, place="shuffle", order="shuffle"))
+    g1 = GpuRx(sc, queue=True); g1.packetize_all()
+    one = run_iteration(g1, sc, 20_000)
+    del g1
+    g2 = GpuRx(sc, queue=True, acc_copies=2, acc_policy=0, acc_place=place); g2.packetize_all()
+    two = run_iteration(g2, sc, 20_000)
+    info = g2.agg.accumulator_info()
+    print("accumulator after the run:", info)
+    assert info["copies"] == (2 if place == 0 else info["copies"])
+    assert np.array_equal(one["out"].view(np.uint32), two["out"].view(np.uint32))
+    assert one["counters"] == two["counters"] and one["rounds"] == two["rounds"]
+    assert two["norm"] == pytest.approx(one["norm"], rel=1e-12)
+    for a, b in zip(one["probes"], two["probes"]):
+        assert np.array_equal(a["missing"], b["missing"]) and np.array_equal(a["list"], b["list"])
+
+
 def test_accumulator_api():
     from paper_2605_01989_amd import DblpError, binding
     sc = build_scenario(mk(2, [1000], 10))
