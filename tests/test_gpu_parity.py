@@ -587,7 +587,7 @@ def test_broadcast_leg_each_receiver_reconstructs_with_zero_fill():
 
 
 # ------------------------------------------------------------------------------ randomized sweep
-@pytest.mark.parametrize("seed", range(32))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_geometry_sweep(seed):
     """Seeded random worker counts, packet lengths, bucket tables, loss rates, placements, orders
     and bounds; two iterations each so the stored previous norm is exercised."""
@@ -603,10 +603,13 @@ def test_random_geometry_sweep(seed):
     place = str(rng.choice(["worker_major", "interleave", "shuffle"]))
     order = str(rng.choice(["identity", "reverse", "shuffle"]))
     w = mk(W, sizes, P, loss, seed=seed, place=place, order=order)
+    # hand-over form and accumulator arrangement rotate with the seed: tables / receive queues,
+    # one copy / second copy only / copies alternating per batch
+    gpu_kw = [dict(), dict(acc_copies=2, acc_policy=2), dict(acc_copies=2, acc_policy=3)][seed % 3]
     prev_o = prev_g = None
     for it in range(2):
         sc = build_scenario(w, it)
-        o, g = both(sc)
+        o, g = both(sc, queue=bool((seed // 3) % 2), **gpu_kw)
         o.o.set_prev_norm(prev_o)
         g.agg.set_prev_norm(prev_g)
         ref = run_iteration(o, sc, ppm)
