@@ -156,6 +156,16 @@ __global__ void reset_counters(u64* __restrict__ c) {
     c[t] = t == C_LO ? NONE64 : 0;
 }
 
+// Start of a round in one launch: bitmap and the gather kernels' per-block rows to zero, counters reset.
+__global__ __launch_bounds__(256) void reset_round(u64* __restrict__ bitmap, u64 n_bitmap, u64* __restrict__ rows, u64 n_rows,
+                                                   u64* __restrict__ counters) {
+    const u64 stride = (u64)gridDim.x * blockDim.x;
+    for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_bitmap + n_rows; i += stride) {
+        if (i < n_bitmap) bitmap[i] = 0; else rows[i - n_bitmap] = 0;
+    }
+    if (blockIdx.x == 0 && threadIdx.x < C_COUNT) counters[threadIdx.x] = threadIdx.x == C_LO ? NONE64 : 0;
+}
+
 // counters[C_ACCEPTED] = sum of the per-block rows written by the gather kernels.  One block.
 __global__ __launch_bounds__(256) void fold_accept_rows(const u64* __restrict__ rows, u32 n, u64* __restrict__ counters) {
     __shared__ u64 sh[256];
@@ -1490,9 +1500,8 @@ extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
     if (c->n_late_held) { HIP_TRY(c, hipStreamSynchronize(c->stream)); release_late_held(c); }   // not kept across rounds
     HIP_TRY(c, hipSetDevice(c->device));
     const u64 n = c->g.W * c->g.words_pw;
-    hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n + 255) / 256, 16)), dim3(256), 0, c->stream, c->d_bitmap, n, 0ull);
-    hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters);
-    hipLaunchKernelGGL(fill_u64, dim3(32), dim3(256), 0, c->stream, c->d_accept_rows, (u64)(2 * ACCEPT_ROWS), 0ull);
+    hipLaunchKernelGGL(reset_round, dim3(grid_for(c, (n + 2 * ACCEPT_ROWS + 255) / 256, 16)), dim3(256), 0, c->stream,
+                       c->d_bitmap, n, c->d_accept_rows, (u64)(2 * ACCEPT_ROWS), c->d_counters);
     LAUNCH_CHECK(c, "begin_round");
     c->round = round; c->round_open = 1; c->finalized = 0;
     return DBLP_OK;
