@@ -169,9 +169,15 @@ __global__ __launch_bounds__(256) void reset_round(u64* __restrict__ bitmap, u64
 // counters[C_ACCEPTED] = sum of the per-block rows written by the gather kernels.  One block.
 __global__ __launch_bounds__(256) void fold_accept_rows(const u64* __restrict__ rows, u32 n, u64* __restrict__ counters) {
     __shared__ u64 sh[256];
-    u64 s = 0;
-    for (u32 i = threadIdx.x; i < n; i += 256) s += rows[i];
-    sh[threadIdx.x] = s;
+    u64 a[8] = {0, 0, 0, 0, 0, 0, 0, 0};          // eight loads in flight per thread
+    for (u32 i = threadIdx.x; i < n; i += 256 * 8) {
+        #pragma unroll
+        for (u32 j = 0; j < 8; ++j) {
+            const u32 k = i + j * 256;
+            a[j] += k < n ? rows[k] : 0;
+        }
+    }
+    sh[threadIdx.x] = ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
     __syncthreads();
     for (u32 d = 128; d > 0; d >>= 1) {
         if (threadIdx.x < d) sh[threadIdx.x] += sh[threadIdx.x + d];
