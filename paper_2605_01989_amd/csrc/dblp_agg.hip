@@ -1277,7 +1277,7 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
         // (a candidate that straddles two thirds is passed over); its contents are scratch here
         const float t_end = time_rw(c, rd, (float*)((uint8_t*)cand + bytes));
         const float t_beg = bytes >= CLS_SCRATCH_BYTES ? time_rw(c, rd, (float*)cand) : t_end;
-        auto differs = [&](float t) { const float hi = t > t_ref ? t : t_ref; return t > 0.f && fabsf(t - t_ref) > 0.05f * hi; };
+        auto differs = [&](float t) { const float hi = t > t_ref ? t : t_ref; return t > 0.f && fabsf(t - t_ref) > 0.07f * hi; };
         c->place_ms[1] = t_end > 0.f ? t_end : 0.f;
         c->place_steps = step + 1;
         if (t_end > 0.f && t_end < t_fastest) t_fastest = t_end;
