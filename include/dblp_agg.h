@@ -107,9 +107,9 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
  *
  * dblp_create chooses two copies when one round carries at least 2 GiB of packets, else one.
  * dblp_accumulator_copies(copies = 1|2, place): reallocates.  place = 1: search for a second
- *   copy in another third than the first: candidates are allocated 8 GiB apart and timed
- *   against the first copy until one differs (temporarily holds up to half of the device
- *   memory; takes from 0.2 s on a fresh device to a few seconds).  If none is found, up to
+ *   copy in another third than the first: candidates are allocated 6 GiB apart and timed
+ *   against the first copy until one differs (temporarily holds up to nine tenths of the device
+ *   memory; takes from 0.2 s on a fresh device to about 7 s).  If none is found, up to
  *   three later attempts are made from dblp_apply_arrivals* under DBLP_ACC_AUTO: when a packet
  *   buffer measures clearly slower against the first copy than another measurement did, one
  *   fresh allocation is timed against that buffer and adopted if it is faster (this is the

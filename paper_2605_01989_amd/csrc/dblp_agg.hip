@@ -1227,8 +1227,8 @@ static float time_rw(dblp_ctx* c, const void* src, float* scratch) {
 // (Re)allocates the accumulator as `copies` copies.  place != 0: search for a second copy in
 // another third of the HBM address space than the first, and have no second copy if none is found.
 // The contents of the round in progress are lost.
-#define PLACE_MAX_STEPS 24
-#define PLACE_STRIDE_BYTES (8ull << 30)
+#define PLACE_MAX_STEPS 40
+#define PLACE_STRIDE_BYTES (6ull << 30)
 static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, DBLP_EHIP, "accumulator_copies: synchronize");
     for (int i = 0; i < 2; ++i) { if (c->acc_alloc[i]) (void)hipFree(c->acc_alloc[i]); c->acc_alloc[i] = nullptr; }
@@ -1256,7 +1256,7 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
     }
     // Walk through the free memory: candidate, then a holder allocation that pushes the next
     // candidate further on, until a candidate measures differently from the first copy against
-    // the same read buffer or half of the memory is held.
+    // the same read buffer or nine tenths of the memory are held.
     // what the probe reads: a buffer allocated right after the first copy (next to its end, where
     // the scratch area that the reference measurement writes lies)
     void* near0 = nullptr;
@@ -1270,7 +1270,7 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
     void* held[2 * PLACE_MAX_STEPS];
     int n_held = 0;
     size_t held_bytes = 0;
-    for (int step = 0; step < PLACE_MAX_STEPS && t_ref > 0.f && held_bytes < total_b / 2; ++step) {
+    for (int step = 0; step < PLACE_MAX_STEPS && t_ref > 0.f && held_bytes < total_b / 10 * 9; ++step) {
         void* cand = nullptr;
         if (hipMalloc(&cand, bytes + scratch) != hipSuccess) { (void)hipGetLastError(); break; }
         // both ends of the candidate must differ from the first copy, and in the same direction
