@@ -50,28 +50,35 @@ class DeviceJob:
     """One workload with every input resident in HBM, driven through the C-ABI binding."""
 
     def __init__(self, w, n_masks: int, place: str | None = None, order: str | None = None, queue: bool = True,
-                 accumulator: str = "auto",
+                 accumulator: str = "one", both_forms_its=(),
                  drawn_rounds: int = BENCH_DRAWN_ROUNDS, per_iteration_retx: bool = False):
-        """drawn_rounds: retransmission rounds whose loss is drawn once (keyed to iteration 0) and kept
+        """accumulator: "one" a single accumulator copy; "pair" a plain second copy; "search" a second
+        copy searched for in another third of HBM (bounded: three fifths of the free memory, 8 s).
+        The result is always left in place (finalize with no output buffer): d_out is a view of the
+        library's first accumulator copy.
+        both_forms_its: iterations whose first transmissions are prepared in both hand-over forms.
+        drawn_rounds: retransmission rounds whose loss is drawn once (keyed to iteration 0) and kept
         on the device.  per_iteration_retx: draw every retransmission round's loss for the iteration
         at hand instead (small workloads whose loss process depends on the iteration)."""
         import torch
         import paper_2605_01989_amd as dblp
         import workloads as wl
+        from paper_2605_01989_amd import binding
         self.torch, self.wl, self.w = torch, wl, w
         L = self.L = w.layout
         self.place, self.order = place or w.place, order or w.order
         self.queue = queue   # first transmissions handed over as receive queues (else mask + order + worker table)
+        self.both_forms_its = set(both_forms_its)
         self.rnd_id = 1
-        self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5))
-        if accumulator == "one":         # for comparison: no second accumulator copy
-            self.agg.accumulator_copies(1)
+        mode = dict(one=binding.ACCMODE_SINGLE, pair=binding.ACCMODE_PAIR, search=binding.ACCMODE_SEARCH)[accumulator]
+        self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5),
+                                   accumulator_mode=mode, search_free_fraction=0.6, search_seconds=8.0)
         self.n_slots = L.W * L.n_pkts
         dev = "cuda"
         t0 = time.time()
         self.packets = torch.empty(self.n_slots * L.stride, dtype=torch.uint8, device=dev)
         self.src = torch.empty(self.n_slots, dtype=torch.int16, device=dev)
-        self.d_out = torch.empty(L.N, dtype=torch.float32, device=dev)
+        self.d_out = self.agg.accumulator_tensor(0)
         self.d_missing = torch.empty(L.W * L.B, dtype=torch.int32, device=dev)
         self.list_cap = max(self.n_slots // 8, 1 << 16)
         self.d_list = torch.empty(self.list_cap, dtype=torch.int64, device=dev)
@@ -140,12 +147,13 @@ class DeviceJob:
         d_s = torch.from_numpy(surv.reshape(-1)).cuda()
         by_slot = torch.zeros(self.n_slots, dtype=torch.uint8, device="cuda")
         by_slot[self.d_slot_of.long()] = d_s
-        lost = int(surv.size - int(surv.sum()))
-        if self.queue:
-            return dict(queues=[self._queue_for(ch, by_slot[ch["base"]: ch["base"] + ch["n"]]) for ch in self.chunks],
-                        lost=lost)
-        out = [self._pack_bits(by_slot[ch["base"]: ch["base"] + ch["n"]]) for ch in self.chunks]
-        return dict(words=out, lost=lost)
+        m = dict(lost=int(surv.size - int(surv.sum())))
+        both = it in self.both_forms_its
+        if self.queue or both:
+            m["queues"] = [self._queue_for(ch, by_slot[ch["base"]: ch["base"] + ch["n"]]) for ch in self.chunks]
+        if not self.queue or both:
+            m["words"] = [self._pack_bits(by_slot[ch["base"]: ch["base"] + ch["n"]]) for ch in self.chunks]
+        return m
 
     def _queue_for(self, ch, alive):
         """Receive queue of one chunk step: slot | worker << 32 for every packet that survived,
@@ -156,6 +164,12 @@ class DeviceJob:
         slots = slots[alive[slots].bool()]
         worker = self.src[ch["base"]: ch["base"] + ch["n"]][slots].long() & 0xFFFF
         return slots | (worker << 32)
+
+    def use_single_accumulator(self):
+        """Switch the context to one accumulator copy (d_out is a view of it: refreshed here)."""
+        self.d_out = None
+        self.agg.accumulator_copies(1)
+        self.d_out = self.agg.accumulator_tensor(0)
 
     # -- the timed path --------------------------------------------------------------------
     def step(self, it: int, bound_ppm: int, scale_ratio: float = 1.0, record: list | None = None) -> dict:
@@ -205,12 +219,18 @@ class DeviceJob:
                     resent = None          # survivors not counted here: the caller derives them from the accepted counter
                 elif resent is not None:
                     resent += count        # a round without drawn loss: everything arrives
-        agg.finalize(self.d_out)
+        agg.finalize(None)        # in place: the result is d_out, the first accumulator copy
         prev = agg.get_prev_norm()
         if prev is not None:
             agg.set_prev_norm(prev * scale_ratio)
         norm, delta, crit = agg.phase_signal()
         return dict(rounds=rounds, resent=resent, norm=norm, rel_delta=delta, critical=crit, lost_first=m["lost"])
+
+
+def default_accumulator(w) -> str:
+    """A second accumulator copy is worth its memory when one round carries at least 2 GiB of packets."""
+    L = w.layout
+    return "search" if L.W * L.n_pkts * L.stride >= 2 << 30 else "one"
 
 
 def next_bound(w, rel_delta: float, critical: bool) -> int:
@@ -233,25 +253,103 @@ def first_bound(w) -> int:
             "three_level": lambda: p["ppm"][0], "linear": lambda: p["lo_ppm"]}[p["kind"]]()
 
 
+def host_description() -> dict:
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
+    return dict(cpu_model=model, nproc=os.cpu_count(), usable_cores=usable,
+                omp_num_threads=os.environ.get("OMP_NUM_THREADS"))
+
+
 def cpu_baseline(w, target_elems: int) -> dict:
     """The oracle, as it stands, timed on this host on a bounded sample of the same workload:
-    same W, P, bucket shape, loss process, placement and order, smaller gradient."""
+    same W, P, bucket shape, loss process, placement and order, smaller gradient.  Timed twice:
+    the plain single-threaded walk (`value`) and the same arithmetic spread over all cores by
+    element range (`all_cores`)."""
     import workloads as wl
     from harness import OracleRx, build_scenario, run_iteration
     ws = w if w.layout.N <= target_elems else wl.scaled_down(w, target_elems)
     sc = build_scenario(ws, 0)
+    L = ws.layout
+    fill = L.N / (L.n_pkts * L.P)
     rx = OracleRx(sc)
     rx.packetize_all()
     t0 = time.perf_counter()
     res = run_iteration(rx, sc, first_bound(ws))
     dt = time.perf_counter() - t0
-    L = ws.layout
-    fill = L.N / (L.n_pkts * L.P)
     payload = res["counters"]["accepted"] * 4 * L.P * fill
+    rx.threads = 0                                  # all cores OpenMP offers; same inputs, same receiver object
+    t0 = time.perf_counter()
+    res_mt = run_iteration(rx, sc, first_bound(ws))
+    dt_mt = time.perf_counter() - t0
+    assert res_mt["counters"] == res["counters"] and np.array_equal(res_mt["out"], res["out"])
     return dict(value=payload / dt / 1e9, unit="GB/s", cores=1, kind="oracle",
                 sample=f"{ws.name}: W={L.W} N={L.N} P={L.P} packets={L.W * L.n_pkts} one iteration "
-                       f"incl. {res['rounds']} retransmission round(s), {dt:.2f} s single-threaded",
-                packets_per_s=res["counters"]["accepted"] / dt)
+                       f"incl. {res['rounds']} retransmission round(s), {dt:.2f} s single-threaded, "
+                       f"{dt_mt:.2f} s on {rx.threads_used} threads",
+                packets_per_s=res["counters"]["accepted"] / dt,
+                all_cores=dict(value=payload / dt_mt / 1e9, unit="GB/s", cores=rx.threads_used,
+                               packets_per_s=res["counters"]["accepted"] / dt_mt,
+                               note="arrival walk split by element range over the threads; finalize and the "
+                                    "norm stay single-threaded"),
+                host=host_description())
+
+
+def run_leg(job, w, its, bounds=None, profile=False) -> dict:
+    """Times the steps `its` (iteration numbers).  bounds: None = the workload's policy decides, starting
+    from `job.next_bound`; a dict iteration -> bound replays a recorded run (the same work again)."""
+    import torch
+    from paper_2605_01989_amd import binding
+    agg = job.agg
+    sched = w.scale_schedule
+
+    def ratio(t):
+        """s_{t-1}/s_t of the gradient-scale schedule (1 at its start and when there is none)."""
+        if not sched or t % len(sched) == 0:
+            return 1.0
+        return sched[t % len(sched) - 1] / sched[t % len(sched)]
+
+    if profile:
+        agg.profile_enable(True)
+        for k in range(binding.K_FINALIZE + 1):
+            agg.profile_read(k)
+    torch.cuda.synchronize()
+    accepted_total, resent_total, rounds_total = 0, 0, 0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t_wall0 = time.perf_counter()
+    ev0.record()
+    per_step = []
+    for t in its:
+        bound = job.next_bound if bounds is None else bounds[t]
+        r = job.step(t, bound, ratio(t))
+        c = agg.get_counters()
+        accepted_total += c["accepted"]
+        # packets that arrived in retransmission rounds = accepted - first-transmission survivors
+        resent = r["resent"] if r["resent"] is not None else c["accepted"] - (job.n_slots - r["lost_first"])
+        resent_total += resent
+        rounds_total += r["rounds"]
+        per_step.append(dict(it=t, bound_ppm=bound, rounds=r["rounds"], resent=resent, accepted=c["accepted"]))
+        job.next_bound = next_bound(w, r["rel_delta"], r["critical"])
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_wall0
+    out = dict(wall=wall, steps=len(its), accepted=accepted_total, resent=resent_total, rounds=rounds_total,
+               per_step=per_step, event_ms=ev0.elapsed_time(ev1))
+    if profile:
+        out["prof"] = {name: agg.profile_read(k) for name, k in
+                       (("index", binding.K_INDEX), ("gather", binding.K_GATHER), ("probe", binding.K_PROBE),
+                        ("finalize", binding.K_FINALIZE))}
+        agg.profile_enable(False)
+    return out
 
 
 def main():
@@ -265,9 +363,13 @@ def main():
     ap.add_argument("--arrivals", default="queue", choices=["queue", "tables"],
                     help="how first transmissions are handed over: one receive queue of descriptors per "
                          "chunk step (default), or mask + order + per-slot worker table")
-    ap.add_argument("--accumulator", default="auto", choices=["auto", "one"],
-                    help="auto: the library's default (two accumulator copies in different thirds of HBM for "
-                         "large workloads); one: a single copy")
+    ap.add_argument("--accumulator", default=None, choices=["search", "pair", "one"],
+                    help="search: a second accumulator copy is searched for in another third of HBM (bounded; "
+                         "one copy when none is found); pair: a plain second copy; one: a single copy.  "
+                         "Default: search when a round carries at least 2 GiB of packets, else one")
+    ap.add_argument("--extra-steps", type=int, default=5,
+                    help="steps of the timed run that are replayed (same masks, same bounds) with the other "
+                         "hand-over form and with a single accumulator copy, reported under other_forms; 0 = none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, "
@@ -282,22 +384,18 @@ def main():
 
     import torch
     import workloads as wl
-    from paper_2605_01989_amd import binding
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     w = wl.workload(args.workload)
     L = w.layout
+    if args.accumulator is None:
+        args.accumulator = default_accumulator(w)
     total = args.warmup + args.steps
+    n_extra = min(args.extra_steps, args.steps)
+    extra_its = list(range(args.warmup, args.warmup + n_extra))
     job = DeviceJob(w, n_masks=total, place=args.place, order=args.order, queue=args.arrivals == "queue",
-                    accumulator=args.accumulator)
+                    accumulator=args.accumulator, both_forms_its=extra_its)
     agg = job.agg
-    sched = w.scale_schedule
-
-    def ratio(t):
-        """s_{t-1}/s_t of the gradient-scale schedule (1 at its start and when there is none)."""
-        if not sched or t % len(sched) == 0:
-            return 1.0
-        return sched[t % len(sched) - 1] / sched[t % len(sched)]
 
     if args.calibrate_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
@@ -305,43 +403,17 @@ def main():
         b.copy_(a)          # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del a, b
-    bound = first_bound(w)
-    for t in range(args.warmup):
-        r = job.step(t, bound, ratio(t))
-        log(f"[bench] warmup {t}: bound={bound} rounds={r['rounds']} delta={r['rel_delta']:.4f}")
-        bound = next_bound(w, r["rel_delta"], r["critical"])
-    agg.profile_enable(True)
-    for k in range(binding.K_FINALIZE + 1):
-        agg.profile_read(k)
-    torch.cuda.synchronize()
-    c0 = None
-    accepted_total, resent_total, rounds_total = 0, 0, 0
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t_wall0 = time.perf_counter()
-    ev0.record()
-    per_step = []
-    for t in range(args.warmup, total):
-        r = job.step(t, bound, ratio(t))
-        c = agg.get_counters()
-        accepted_total += c["accepted"]
-        # packets that arrived in retransmission rounds = accepted - first-transmission survivors
-        resent = r["resent"] if r["resent"] is not None else c["accepted"] - (job.n_slots - r["lost_first"])
-        resent_total += resent
-        rounds_total += r["rounds"]
-        per_step.append(dict(bound_ppm=bound, rounds=r["rounds"], resent=resent, accepted=c["accepted"]))
-        bound = next_bound(w, r["rel_delta"], r["critical"])
-    ev1.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t_wall0
+    job.next_bound = first_bound(w)
+    warm = run_leg(job, w, list(range(args.warmup)))
+    for st in warm["per_step"]:
+        log(f"[bench] warmup {st['it']}: bound={st['bound_ppm']} rounds={st['rounds']}")
+    main_leg = run_leg(job, w, list(range(args.warmup, total)), profile=True)
+    wall, prof = main_leg["wall"], main_leg["prof"]
+    accepted_total = main_leg["accepted"]
     ms_per_step = wall * 1e3 / args.steps
-    prof = {name: agg.profile_read(k) for name, k in
-            (("index", binding.K_INDEX), ("gather", binding.K_GATHER), ("probe", binding.K_PROBE),
-             ("finalize", binding.K_FINALIZE))}
-    agg.profile_enable(False)
 
     fill = L.N / (L.n_pkts * L.P)
-    payload_bytes = accepted_total * 4 * L.P * fill
-    value = payload_bytes / wall / 1e9
+    value = accepted_total * 4 * L.P * fill / wall / 1e9
     # dominant kernel: gather_accumulate.  Algorithmic bytes = every accepted packet read once
     # (header + payload + padding = stride) + the accumulator written once per iteration.
     g_ms, g_n = prof["gather"]
@@ -353,10 +425,38 @@ def main():
                     launches=g_n, avg_launch_ms=round(g_ms / max(g_n, 1), 4),
                     algorithmic_bytes_per_launch=round(g_bytes / max(g_n, 1)),
                     traffic=None if ratio_pmc is None else round(ratio_pmc * g_bytes / max(g_n, 1)))
-    # whole-path algorithmic bytes: + finalize (read acc, write out) per iteration
-    path_bytes = g_bytes + args.steps * 8 * L.N
+    # whole-path algorithmic bytes: the gather's (packets read once, accumulator written once).  The
+    # mean and the sum of squares are formed in the same pass and the result is left in place, so the
+    # compensation pass adds no bytes of its own beyond the spans it zeroes or moves.
+    path_bytes = g_bytes
+    survey_bytes = g_bytes + args.steps * 8 * L.N     # what a separate read-scale-write finalize pass would add
     acc_info = agg.accumulator_info()
     acc_info.pop("last_pick")
+    acc_info["mode"] = args.accumulator
+
+    def leg_summary(leg):
+        acc = leg["accepted"]
+        return dict(ms_per_step=round(leg["wall"] * 1e3 / leg["steps"], 3), steps=leg["steps"],
+                    value=round(acc * 4 * L.P * fill / leg["wall"] / 1e9, 2),
+                    packets_per_s=round(acc / leg["wall"], 1),
+                    path_hbm_frac=round((acc * L.stride + leg["steps"] * 4 * L.N) / leg["wall"] / 1e9 / HBM_PEAK_GBPS, 4))
+
+    other = {}
+    if n_extra:
+        bounds = {st["it"]: st["bound_ppm"] for st in main_leg["per_step"]}
+        ref_leg = dict(main_leg, per_step=main_leg["per_step"][:n_extra])
+        other[f"{args.arrivals}+{args.accumulator} (the timed run, its first {n_extra} steps replayed)"] = \
+            leg_summary(run_leg(job, w, extra_its, bounds))
+        job.queue = not job.queue
+        name = "tables" if args.arrivals == "queue" else "queue"
+        other[f"{name}+{args.accumulator}"] = leg_summary(run_leg(job, w, extra_its, bounds))
+        job.queue = not job.queue
+        if acc_info["copies"] == 2:
+            job.use_single_accumulator()
+            run_leg(job, w, extra_its[:1], bounds)          # one untimed step on the new copy
+            other[f"{args.arrivals}+one"] = leg_summary(run_leg(job, w, extra_its, bounds))
+        del ref_leg
+
     out = dict(metric="aggregated_gradient_GBps", value=round(value, 2), unit="GB/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 3),
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32", data="synthetic",
@@ -364,14 +464,15 @@ def main():
                                     f"packets/round={L.W * L.n_pkts} loss={w.loss['kind']} "
                                     f"policy={w.policy['kind']}",
                            placement=job.place, arrival_order=job.order, arrivals=args.arrivals,
-                           accumulator=acc_info,
+                           accumulator=acc_info, result="in place (first accumulator copy)",
                            chunk_steps=len(job.chunks), resident_packet_GB=round(job.packets.numel() / 1e9, 2)),
                packets_per_s=round(accepted_total / wall, 1),
                path_hbm_frac=round(path_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),
-               retransmission_rounds=rounds_total, resent_packets=resent_total,
-               gpu_event_ms_per_step=round(ev0.elapsed_time(ev1) / args.steps, 3),
+               path_hbm_frac_counting_a_separate_finalize_pass=round(survey_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),
+               retransmission_rounds=main_leg["rounds"], resent_packets=main_leg["resent"],
+               gpu_event_ms_per_step=round(main_leg["event_ms"] / args.steps, 3),
                kernel_ms_per_step={k: round(v[0] / args.steps, 4) for k, v in prof.items()},
-               per_step=per_step, roofline=roofline)
+               other_forms=other, per_step=main_leg["per_step"], roofline=roofline)
     if not args.no_cpu_baseline:
         del job
         torch.cuda.empty_cache()

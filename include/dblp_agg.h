@@ -21,10 +21,12 @@
  *   - All work is enqueued on the hipStream_t given at creation (passed as
  *     void*).  Calls are asynchronous except those that return host scalars
  *     (dblp_loss_account, dblp_phase_signal, dblp_get_counters,
- *     dblp_packetize), which synchronise that stream; dblp_accumulator_copies
- *     does too, and so does dblp_apply_arrivals* the first time it sees a
- *     packet buffer of 1 GiB or more while the accumulator policy is AUTO
- *     (see "The accumulator and where it lives").
+ *     dblp_packetize with a slot map, dblp_packetize_list), which synchronise
+ *     that stream; dblp_accumulator_copies does too.  dblp_apply_arrivals*
+ *     never allocate and never wait, with one exception that the caller opts
+ *     into: a context with TWO library-owned accumulator copies under the
+ *     policy DBLP_ACC_AUTO times a probe kernel the first time it sees a packet
+ *     buffer of 1 GiB or more (see "The accumulator and where it lives").
  *   - A context is not thread-safe; use one per host thread.
  *
  * Geometry.  The gradient has N fp32 elements, tiled in order by B buckets
@@ -79,14 +81,28 @@ typedef struct {
     double eta;              /* Eq. 1 threshold; the paper uses 0.5 */
     int device;              /* HIP device ordinal */
     void* stream;            /* hipStream_t; NULL = the null stream */
+    /* The accumulator (see "The accumulator and where it lives"); all zero = one copy that the
+     * library allocates. */
+    int accumulator_mode;        /* DBLP_ACCMODE_SINGLE, _PAIR or _SEARCH */
+    float* d_accumulator[2];     /* caller-owned DEVICE buffers of n_elems floats, 256-byte aligned, or
+                                    NULL: [0] the accumulator, [1] the second copy (PAIR only).  They stay
+                                    the caller's and must outlive the context. */
+    double search_free_fraction; /* SEARCH: share of the memory that is FREE when dblp_create runs that the
+                                    search may hold at once, 0 < f <= 0.9; 0 = 0.5 */
+    double search_seconds;       /* SEARCH: time limit of the search; 0 = 2 seconds */
 } dblp_config;
 
+#define DBLP_ACCMODE_SINGLE 0 /* one accumulator */
+#define DBLP_ACCMODE_PAIR 1   /* two copies, the second a plain allocation (or d_accumulator[1]) */
+#define DBLP_ACCMODE_SEARCH 2 /* two copies, the second searched for in another third of HBM; one copy if none is found */
+
 /* Allocates the context and its device state (bitmap W x ceil(n_pkts/64) words, arrival
- * index W x n_pkts x 8 bytes, accumulator N floats in one or two copies, one byte per packet
- * sequence number, per-bucket counters).  For workloads of 2 GiB per round or more it also
- * searches for the second accumulator copy (see below), which takes 0.2 s to a few seconds.
- * *out is set only on success.  Errors: EINVAL (bad table, W too large, n_pkts >= 2^32),
- * ENOMEM, EHIP. */
+ * index W x n_pkts x 8 bytes, accumulator N floats in one or two copies unless the caller
+ * supplies them, one byte per packet sequence number, per-bucket counters).  Under
+ * DBLP_ACCMODE_SEARCH it also searches for the second accumulator copy (see below) within the
+ * limits given in the configuration.  *out is set only on success.  Errors: EINVAL (bad table,
+ * W too large, n_pkts >= 2^32, unknown mode, misaligned or inconsistent caller buffers), ENOMEM,
+ * EHIP. */
 int dblp_create(dblp_ctx** out, const dblp_config* cfg);
 
 /* Frees everything the context owns.  NULL is accepted. */
@@ -100,35 +116,43 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
 /* The accumulator and where it lives.  Not in the paper: a property of this memory system.
  * A payload stream with a few percent of result writes mixed in runs about 15 % slower on
  * MI355X when reads and writes fall into the same third of the HBM address space than when
- * they fall into different thirds.  The library can keep the accumulator (N floats) in two
- * copies in different thirds; the spans a batch writes for the first time go to the copy that
- * is faster for that batch's packet buffer, later batches update a span where it lives, and
- * dblp_finalize reads each span from its copy.  Results do not depend on any of this.
+ * they fall into different thirds.  A context can therefore keep the accumulator (N floats) in
+ * two copies: the spans a batch writes for the first time go to one of them, later batches
+ * update a span where it lives, and dblp_finalize reads each span from its copy.  Results do
+ * not depend on any of this.  The caller decides (dblp_config.accumulator_mode):
+ *   DBLP_ACCMODE_SINGLE  one copy (the default).  Nothing is measured, nothing is searched.
+ *   DBLP_ACCMODE_PAIR    a second copy, allocated plainly or supplied by the caller.
+ *   DBLP_ACCMODE_SEARCH  a second copy in another third than the first: candidates are
+ *       allocated 6 GiB apart and a probe kernel is timed writing to each until one differs
+ *       from the first copy.  The search holds at most search_free_fraction of the memory that
+ *       was free when it started, stops after search_seconds, and releases everything but the
+ *       copy it adopts; when it finds none the context has one copy (dblp_accumulator_info
+ *       tells).  Both copies are the library's (d_accumulator must be NULL).
+ * Caller-owned buffers (d_accumulator): [0] becomes the accumulator, which makes
+ * dblp_finalize(d_out = that buffer) an in-place operation; [1] is used under PAIR.  The
+ * library never measures caller-owned buffers: with them DBLP_ACC_AUTO behaves as
+ * DBLP_ACC_FIRST.
  *
- * dblp_create chooses two copies when one round carries at least 2 GiB of packets, else one.
- * dblp_accumulator_copies(copies = 1|2, place): reallocates.  place = 1: search for a second
- *   copy in another third than the first: candidates are allocated 6 GiB apart and timed
- *   against the first copy until one differs (temporarily holds up to nine tenths of the device
- *   memory; takes from 0.2 s on a fresh device to about 7 s).  If none is found, up to
- *   three later attempts are made from dblp_apply_arrivals* under DBLP_ACC_AUTO: when a packet
- *   buffer measures clearly slower against the first copy than another measurement did, one
- *   fresh allocation is timed against that buffer and adopted if it is faster (this is the
- *   only case in which those calls allocate).  place = 2: no search now, only the later
- *   attempts.  place = 0: plain second allocation, kept regardless.  Synchronises the stream;
- *   discards the round in progress (call dblp_begin_round again).  ENOMEM if not even one
- *   copy fits; the context then has no accumulator and dblp_begin_round returns ESTATE until
- *   a later dblp_accumulator_copies succeeds.
- * dblp_accumulator_policy: DBLP_ACC_AUTO (default) times a read+write probe kernel on the
- *   first batch seen from each packet buffer of at least 1 GiB (about 3 ms once per buffer,
- *   synchronising the stream; the probe reads d_packets[0 .. n_slots * stride) and nothing
- *   else of the caller's) and remembers the answer for the last 32 buffers; smaller or thinly
- *   used buffers use the first copy.  FIRST / SECOND force a copy, ALTERNATE switches on
- *   every batch (for tests).  Because AUTO waits for events on the stream, select FIRST or
- *   SECOND before calling dblp_apply_arrivals* on a stream that is being captured.
+ * dblp_accumulator_copies(copies = 1|2, place) reallocates library-owned copies later: place
+ *   = 0 plain allocation, 1 the bounded search described above.  Synchronises the stream and
+ *   discards the round in progress (call dblp_begin_round again).  EINVAL on a context with
+ *   caller-owned buffers.  ENOMEM if not even one copy fits; the context then has no
+ *   accumulator and dblp_begin_round returns ESTATE until a later call succeeds.
+ * dblp_accumulator_policy: which copy the spans that a batch writes first go to.
+ *   DBLP_ACC_AUTO (default): with two library-owned copies, the first batch seen from each
+ *   packet buffer of at least 1 GiB is preceded by a timed probe kernel (about 3 ms once per
+ *   buffer, synchronising the stream; it reads d_packets[0 .. n_slots * stride) and writes a
+ *   scratch area that the library keeps behind each copy) and the answer is remembered for the
+ *   last 32 buffers; smaller or thinly used buffers, and contexts with one copy or with
+ *   caller-owned copies, use the first copy without measuring.  FIRST / SECOND force a copy,
+ *   ALTERNATE switches on every batch (for tests).  Select FIRST or SECOND before calling
+ *   dblp_apply_arrivals* on a stream that is being captured.
  * dblp_accumulator_info: number of copies, whether they were measured to lie in different
- *   thirds, the copy the last batch wrote new spans to, and the placement measurement itself
+ *   thirds, the copy the last batch wrote new spans to, and the placement measurement
  *   (placement_ms[0], [1]: probe time in ms writing to the first / second copy, 0 if not
- *   taken; [2]: candidates the placement search tried; [3]: later attempts made so far).  Any pointer may be NULL. */
+ *   taken; [2]: candidates the search tried; [3]: seconds the search took).  Any pointer may be NULL.
+ * dblp_accumulator_ptr: device address of copy `which` (0 or 1; EINVAL if it does not exist).
+ *   Copy 0 holds the result after an in-place dblp_finalize. */
 #define DBLP_ACC_AUTO 0
 #define DBLP_ACC_FIRST 1
 #define DBLP_ACC_SECOND 2
@@ -137,6 +161,7 @@ int dblp_accumulator_copies(dblp_ctx* ctx, int copies, int place);
 int dblp_accumulator_policy(dblp_ctx* ctx, int policy);
 int dblp_accumulator_info(const dblp_ctx* ctx, int* copies, int* distinct_thirds, int* last_pick,
                           double placement_ms[4]);
+int dblp_accumulator_ptr(const dblp_ctx* ctx, int which, float** d_copy);
 
 /* Alg. "DBLP_RECV", initialisation: empty bitmap, nothing received, counters zero; `round`
  * is the round counter that arriving packets must carry.  The accumulator is not cleared:
@@ -212,9 +237,17 @@ int dblp_loss_account(dblp_ctx* ctx, uint32_t bound_ppm, uint32_t* d_missing, ui
                       uint64_t retx_capacity, uint64_t* h_retx_count, int* h_all_met);
 
 /* Alg. "DBLP_RECV" last statements + Alg. "Server" mean: d_out[e] = acc[e] / W where
- * unreceived chunks count as zero (a span no worker delivered is exactly 0).  d_out: 16-byte aligned, N
- * floats.  Also accumulates sum(d_out^2) for dblp_phase_signal.  Only
- * DBLP_COMP_ZEROFILL_MEAN is defined by the paper; other values give EINVAL. */
+ * unreceived chunks count as zero (a span no worker delivered is exactly 0).  d_out: 16-byte
+ * aligned, N floats.  Only DBLP_COMP_ZEROFILL_MEAN is defined by the paper; other values give
+ * EINVAL.  When W is a power of two the division is exact and is applied as the payloads are
+ * summed, so the first accumulator copy already holds the mean of what arrived; then
+ *   d_out == NULL, or d_out == the first accumulator copy (dblp_accumulator_ptr, or the
+ *   caller's d_accumulator[0]): IN PLACE.  Only spans that nobody delivered are written (zeros)
+ *   and spans that live in the second copy are moved over; the result is read from copy 0.
+ *   With W not a power of two this form returns EINVAL.
+ *   any other d_out: the mean is written there (one read and one write of N floats).
+ * Arrivals may still be applied after a finalize (then finalize again).  The sum of squares of
+ * the result is kept for dblp_phase_signal. */
 int dblp_finalize(dblp_ctx* ctx, int compensation, float* d_out);
 
 /* Eq. 1: norm = ||G_curr||_2 of the aggregated gradient; rel_delta = | ||G_prev|| - norm | /

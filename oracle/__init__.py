@@ -20,7 +20,7 @@ def build(force: bool = False) -> str:
     so = os.path.join(_HERE, "libdblp_oracle.so")
     src = os.path.join(_HERE, "dblp_oracle.c")
     if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(src):
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-shared", "-fPIC",
+        subprocess.check_call(["gcc", "-O2", "-std=c11", "-fopenmp", "-Wall", "-Wextra", "-shared", "-fPIC",
                                "-o", so, src, "-lm"])
     return so
 
@@ -39,7 +39,11 @@ def lib():
         L.oracle_begin_round.argtypes = [vp, u16]
         L.oracle_packetize.restype = i32
         L.oracle_packetize.argtypes = [vp, u32, u16, vp, u64, u64, u64, u64, vp, u64, vp, u64, vp]
+        L.oracle_write_headers.restype = i32
+        L.oracle_write_headers.argtypes = [vp, u32, u16, u64, u64, vp, u64, vp, vp]
         L.oracle_apply_arrivals.argtypes = [vp, vp, u64, vp, u64, vp, vp, u64, i32]
+        L.oracle_apply_arrivals_mt.restype = i32
+        L.oracle_apply_arrivals_mt.argtypes = [vp, vp, u64, vp, u64, vp, vp, u64, i32, i32]
         L.oracle_loss_account.argtypes = [vp, u32, vp, vp, u64, vp, vp]
         L.oracle_finalize.argtypes = [vp, vp]
         L.oracle_phase_signal.argtypes = [vp, vp, vp, vp, vp]
@@ -97,8 +101,22 @@ class Oracle:
         if rc != 0:
             raise ValueError("oracle_packetize: packet outside the gradient window")
 
+    def write_headers(self, w, rnd, first_seq, n, headers, src_worker, slot_map=None, slot_base=0):
+        """The 8 header bytes of packets first_seq .. first_seq + n - 1 of worker w, one per slot of
+        `headers` (uint8, 8 bytes per slot): the input of apply_arrivals(accumulate=False, stride=8)."""
+        assert headers.dtype == np.uint8 and src_worker.dtype == np.uint16
+        if slot_map is not None:
+            slot_map = np.ascontiguousarray(slot_map, dtype=np.uint32)
+            assert slot_map.size == n
+        rc = lib().oracle_write_headers(self._h, w, rnd & 0xFFFF, first_seq, n, _p(slot_map), slot_base,
+                                        _p(headers), _p(src_worker))
+        if rc != 0:
+            raise ValueError("oracle_write_headers: sequence number out of range")
+
     def apply_arrivals(self, packets, src_worker, n_slots, mask=None, order=None, n_arrivals=None,
-                       accumulate=True, stride=None):
+                       accumulate=True, stride=None, threads=None):
+        """threads: None = the plain single-threaded walk; an integer = the element-range-parallel
+        walk on that many threads (0: all that OpenMP offers); returns the number used."""
         if mask is not None:
             mask = np.ascontiguousarray(mask, dtype=np.uint64)
             assert mask.size * 64 >= n_slots
@@ -109,8 +127,13 @@ class Oracle:
             assert order.size >= n_arrivals
         elif n_arrivals is None:
             n_arrivals = n_slots
+        if threads is not None:
+            return int(lib().oracle_apply_arrivals_mt(self._h, _p(packets), stride or self.stride, _p(src_worker),
+                                                      n_slots, _p(mask), _p(order), n_arrivals, int(accumulate),
+                                                      int(threads)))
         lib().oracle_apply_arrivals(self._h, _p(packets), stride or self.stride, _p(src_worker), n_slots,
                                     _p(mask), _p(order), n_arrivals, int(accumulate))
+        return 1
 
     def loss_account(self, bound_ppm: int, capacity: int | None = None):
         cap = self.W * self.n_pkts if capacity is None else capacity

@@ -34,6 +34,9 @@
  *   missing * 10^6 <= bound_ppm * packets_in_bucket; the first iteration (no
  *   previous norm, or a zero one) counts as critical.
  *
+ * oracle_apply_arrivals_mt is the same receiver step spread over threads by element range
+ * (used only to time the baseline on all cores; pinned equal to the plain walk).
+ *
  * Arithmetic: sums, mean and norm in IEEE double.  Parity status: every
  * function here is pinned by tests/test_oracle_*.py (brute force over all
  * masks and permutations, closed forms, the paper's constants) except the
@@ -45,6 +48,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 typedef struct {
     uint32_t W;          /* workers */
@@ -159,6 +165,29 @@ int oracle_packetize(const oracle_t* o, uint32_t w, uint16_t round, const float*
 }
 
 /*
+ * The headers alone of the same packets (Sec. "Metadata": sequence number, round counter,
+ * data length), 8 bytes per slot and nothing else: what a receiver that only keeps the
+ * books needs (oracle_apply_arrivals with accumulate == 0 and stride 8).  Same slot rule as
+ * oracle_packetize; no gradient is needed because the length of a packet follows from its
+ * sequence number.  Returns 0, or -1 if a sequence number is out of range.
+ */
+int oracle_write_headers(const oracle_t* o, uint32_t w, uint16_t round, uint64_t first_seq, uint64_t n,
+                         const uint32_t* slot_map, uint64_t slot_base, uint8_t* headers, uint16_t* src_worker) {
+    for (uint64_t i = 0; i < n; ++i) {
+        uint64_t seq = first_seq + i, elem; uint32_t len;
+        if (seq >= o->n_pkts) return -1;
+        packet_span(o, seq, &elem, &len);
+        uint64_t slot = slot_map ? slot_map[i] : slot_base + i;
+        uint8_t* p = headers + slot * 8;
+        p[0] = (uint8_t)(seq); p[1] = (uint8_t)(seq >> 8); p[2] = (uint8_t)(seq >> 16); p[3] = (uint8_t)(seq >> 24);
+        p[4] = (uint8_t)(round); p[5] = (uint8_t)(round >> 8);
+        p[6] = (uint8_t)(len); p[7] = (uint8_t)(len >> 8);
+        src_worker[slot] = (uint16_t)w;
+    }
+    return 0;
+}
+
+/*
  * Receiver (Alg. DBLP_RECV, the chunk-arrival branch), for one batch of
  * arrivals.  order[k] is the slot of the k-th arrival (NULL: k itself);
  * mask bit s (NULL: all ones) says whether slot s survived the network, a lost
@@ -193,6 +222,67 @@ void oracle_apply_arrivals(oracle_t* o, const uint8_t* packets, uint64_t stride,
             }
         }
     }
+}
+
+/*
+ * The same batch on several threads, for the all-cores timing of the baseline.  Thread t owns
+ * the sequence numbers [t * n_pkts / T, (t + 1) * n_pkts / T), i.e. a disjoint element range of
+ * the reconstruction buffer; every thread walks ALL arrivals in arrival order and handles the
+ * ones whose header names a sequence number it owns (thread 0 also takes the arrivals whose
+ * sequence number or slot is out of range).  Each packet is therefore classified exactly once,
+ * by the same tests in the same order as in oracle_apply_arrivals, first copies still win, and
+ * every element receives its addends in arrival order: bitmap, counters and sums are identical
+ * to the single-threaded walk (pinned in tests/test_oracle_pins.py).  n_threads <= 0: as many as
+ * OpenMP offers.  Returns the number of threads used.
+ */
+int oracle_apply_arrivals_mt(oracle_t* o, const uint8_t* packets, uint64_t stride,
+                             const uint16_t* src_worker, uint64_t n_slots, const uint64_t* mask,
+                             const uint32_t* order, uint64_t n_arrivals, int accumulate, int n_threads) {
+    int used = 1;
+    uint64_t accepted = 0, duplicate = 0, stale = 0, invalid = 0;
+#ifdef _OPENMP
+    if (n_threads <= 0) n_threads = omp_get_max_threads();
+#else
+    n_threads = 1;
+#endif
+    #pragma omp parallel num_threads(n_threads) reduction(+ : accepted, duplicate, stale, invalid)
+    {
+        int T = 1, t = 0;
+#ifdef _OPENMP
+        T = omp_get_num_threads(); t = omp_get_thread_num();
+#endif
+        #pragma omp single
+        used = T;
+        const uint64_t own_lo = o->n_pkts * (uint64_t)t / (uint64_t)T, own_hi = o->n_pkts * (uint64_t)(t + 1) / (uint64_t)T;
+        for (uint64_t k = 0; k < n_arrivals; ++k) {
+            uint64_t s = order ? order[k] : k;
+            if (s >= n_slots) { if (t == 0) invalid++; continue; }
+            if (mask && !((mask[s >> 6] >> (s & 63)) & 1)) continue;
+            const uint8_t* p = packets + s * stride;
+            uint32_t seq = (uint32_t)p[0] | (uint32_t)p[1] << 8 | (uint32_t)p[2] << 16 | (uint32_t)p[3] << 24;
+            if (seq < o->n_pkts ? (seq < own_lo || seq >= own_hi) : t != 0) continue;    /* another thread's */
+            uint16_t rnd = (uint16_t)(p[4] | p[5] << 8);
+            uint16_t len = (uint16_t)(p[6] | p[7] << 8);
+            uint32_t w = src_worker[s];
+            if (rnd != o->round) { stale++; continue; }
+            if (w >= o->W || seq >= o->n_pkts) { invalid++; continue; }
+            uint64_t elem; uint32_t want;
+            packet_span(o, seq, &elem, &want);
+            if (len != want) { invalid++; continue; }
+            uint8_t* bit = &o->received[(uint64_t)w * o->n_pkts + seq];
+            if (*bit) { duplicate++; continue; }
+            *bit = 1;
+            accepted++;
+            if (accumulate) {
+                for (uint32_t j = 0; j < len; ++j) {
+                    float v; memcpy(&v, p + 8 + 4 * (size_t)j, 4);
+                    o->acc[elem + j] += (double)v;
+                }
+            }
+        }
+    }
+    o->accepted += accepted; o->duplicate += duplicate; o->stale += stale; o->invalid += invalid;
+    return used;
 }
 
 /*

@@ -19,8 +19,9 @@ _NAMES = {EINVAL: "DBLP_EINVAL", ENOMEM: "DBLP_ENOMEM", ECAPACITY: "DBLP_ECAPACI
 COMP_ZEROFILL_MEAN = 0
 K_INDEX, K_GATHER, K_PROBE, K_FINALIZE = 0, 1, 2, 3
 ACC_AUTO, ACC_FIRST, ACC_SECOND, ACC_ALTERNATE = 0, 1, 2, 3
+ACCMODE_SINGLE, ACCMODE_PAIR, ACCMODE_SEARCH = 0, 1, 2
 
-EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_accumulator_copies", "dblp_accumulator_policy", "dblp_accumulator_info", "dblp_begin_round", "dblp_packetize", "dblp_packetize_list",
+EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_accumulator_copies", "dblp_accumulator_policy", "dblp_accumulator_info", "dblp_accumulator_ptr", "dblp_begin_round", "dblp_packetize", "dblp_packetize_list",
            "dblp_apply_arrivals", "dblp_apply_arrivals_queue", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
            "dblp_get_bitmap", "dblp_get_counters", "dblp_set_prev_norm", "dblp_get_prev_norm",
            "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear", "dblp_clr_init", "dblp_clr_step"]
@@ -47,7 +48,9 @@ class _Config(ctypes.Structure):
     _fields_ = [("n_workers", ctypes.c_uint32), ("payload_floats", ctypes.c_uint32),
                 ("n_elems", ctypes.c_uint64), ("n_buckets", ctypes.c_uint32),
                 ("buckets", ctypes.POINTER(_Bucket)), ("eta", ctypes.c_double),
-                ("device", ctypes.c_int), ("stream", ctypes.c_void_p)]
+                ("device", ctypes.c_int), ("stream", ctypes.c_void_p),
+                ("accumulator_mode", ctypes.c_int), ("d_accumulator", ctypes.c_void_p * 2),
+                ("search_free_fraction", ctypes.c_double), ("search_seconds", ctypes.c_double)]
 
 
 _lib = None
@@ -69,6 +72,7 @@ def lib():
         L.dblp_accumulator_copies.argtypes = [vp, i32, i32]
         L.dblp_accumulator_policy.argtypes = [vp, i32]
         L.dblp_accumulator_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(dbl)]
+        L.dblp_accumulator_ptr.argtypes = [vp, i32, ctypes.POINTER(vp)]
         L.dblp_packetize.argtypes = [vp, u32, u16, vp, u64, u64, u64, u64, vp, u64, u64, vp, vp]
         L.dblp_packetize_list.argtypes = [vp, u16, ctypes.POINTER(vp), vp, u64, u64, u64, vp, vp]
         L.dblp_apply_arrivals.argtypes = [vp, vp, vp, u64, vp, vp, u64]
@@ -132,14 +136,20 @@ def _ptr(t):
 class Aggregator:
     """One dblp_ctx.  Methods mirror the C entry points one to one."""
 
-    def __init__(self, n_workers, n_elems, payload_floats, bucket_off, bucket_cnt, eta=0.5, device=0, stream=None):
+    def __init__(self, n_workers, n_elems, payload_floats, bucket_off, bucket_cnt, eta=0.5, device=0, stream=None,
+                 accumulator_mode=ACCMODE_SINGLE, d_accumulator=(None, None), search_free_fraction=0.0,
+                 search_seconds=0.0):
+        """d_accumulator: up to two caller-owned device tensors of n_elems floats (kept alive here)."""
         import torch
         off = np.asarray(bucket_off, dtype=np.uint64)
         cnt = np.asarray(bucket_cnt, dtype=np.uint64)
         arr = (_Bucket * off.size)(*[_Bucket(int(o), int(c)) for o, c in zip(off, cnt)])
         if stream is None:
             stream = torch.cuda.current_stream(device).cuda_stream
-        cfg = _Config(n_workers, payload_floats, n_elems, off.size, arr, eta, device, stream)
+        self._caller_acc = tuple(d_accumulator)
+        acc = (ctypes.c_void_p * 2)(*[_ptr(t) for t in self._caller_acc])
+        cfg = _Config(n_workers, payload_floats, n_elems, off.size, arr, eta, device, stream,
+                      accumulator_mode, acc, search_free_fraction, search_seconds)
         h = ctypes.c_void_p()
         rc = lib().dblp_create(ctypes.byref(h), ctypes.byref(cfg))
         if rc != OK:
@@ -187,9 +197,23 @@ class Aggregator:
                                               n_slots, _ptr(d_packets), _ptr(d_src_worker)))
 
     def accumulator_copies(self, copies: int, place: int = 0):
-        """place: 0 plain second allocation, 1 search for one in another third of HBM now (and later
-        if none is found), 2 only the later attempts against the caller's packet buffers."""
+        """place: 0 plain second allocation, 1 bounded search for one in another third of HBM."""
         self._check(lib().dblp_accumulator_copies(self._h, copies, int(place)))
+
+    def accumulator_ptr(self, which: int = 0) -> int:
+        p = ctypes.c_void_p()
+        self._check(lib().dblp_accumulator_ptr(self._h, which, ctypes.byref(p)))
+        return int(p.value)
+
+    def accumulator_tensor(self, which: int = 0):
+        """A torch view (no copy) of accumulator copy `which`: after an in-place finalize, copy 0 is
+        the aggregated gradient.  Valid while the context lives and its copies are not reallocated."""
+        import torch
+
+        class _View:
+            __cuda_array_interface__ = dict(shape=(self.N,), typestr="<f4", data=(self.accumulator_ptr(which), False),
+                                            version=2, strides=None)
+        return torch.as_tensor(_View(), device=self.device)
 
     def accumulator_policy(self, policy: int):
         self._check(lib().dblp_accumulator_policy(self._h, policy))
@@ -198,7 +222,8 @@ class Aggregator:
         n, d, p, ms = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), (ctypes.c_double * 4)()
         self._check(lib().dblp_accumulator_info(self._h, ctypes.byref(n), ctypes.byref(d), ctypes.byref(p), ms))
         return dict(copies=n.value, distinct_thirds=bool(d.value), last_pick=p.value,
-                    placement_ms=[round(ms[0], 4), round(ms[1], 4)], placement_steps=int(ms[2]), late_attempts=int(ms[3]))
+                    placement_ms=[round(ms[0], 4), round(ms[1], 4)], placement_steps=int(ms[2]),
+                    placement_seconds=round(ms[3], 3))
 
     def apply_arrivals(self, d_packets, d_src_worker, n_slots, d_mask_words=None, d_order=None, n_arrivals=None):
         if n_arrivals is None:
@@ -219,7 +244,8 @@ class Aggregator:
                                                  ctypes.byref(count), ctypes.byref(met)), allow=(ECAPACITY,))
         return int(count.value), bool(met.value), rc == ECAPACITY
 
-    def finalize(self, d_out, compensation=COMP_ZEROFILL_MEAN):
+    def finalize(self, d_out=None, compensation=COMP_ZEROFILL_MEAN):
+        """d_out None: in place (the result is accumulator copy 0)."""
         self._check(lib().dblp_finalize(self._h, compensation, _ptr(d_out)))
 
     def phase_signal(self, d_vec=None):

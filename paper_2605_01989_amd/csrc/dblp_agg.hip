@@ -19,14 +19,17 @@
 //
 // The probe (Sec. "Dynamically Changing Loss Tolerance"): loss_count (popcount of bitmap words +
 // DPP wave reduction), scan_need (exclusive prefix of the per-(worker,bucket) list lengths) and
-// emit_retx (ordered compaction).  finalize_mean applies the zero-fill/mean of Alg. "Server" and
-// produces the partial sums of squares that Eq. 1 needs; reduce_partials finishes the norm.
+// emit_retx (ordered compaction).  The mean of Alg. "Server" is formed as the payloads are summed when
+// W is a power of two (the division is exact), and the gather kernels keep the sum of squares of
+// what they store, so finalize_pass only writes zeros where nothing arrived (and moves or copies
+// spans where the result is wanted elsewhere); for other W it divides and squares itself.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <time.h>
 
 #include <new>
 #include <vector>
@@ -463,11 +466,13 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
                                                                     float* acc0, float* acc1,
                                                                     uint8_t* __restrict__ home, u32 pick,
                                                                     const u64* __restrict__ counters,
-                                                                    u64* __restrict__ accept_rows, int only_if_sparse) {
+                                                                    u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows,
+                                                                    float inv_w, int only_if_sparse) {
     extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB]
     __shared__ u64 sh_elem[SUB];
     __shared__ u32 sh_len[SUB];
     __shared__ u32 sh_new[GA_WAVES], sh_old[GA_WAVES];
+    __shared__ double sh_sq[GA_WAVES];
     const u64 lo = counters[C_LO], hi = counters[C_HI];
     if (hi == 0) return;                                    // no candidate in this batch
     if (only_if_sparse && !batch_is_sparse(counters, g.W)) return;
@@ -477,6 +482,7 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
     const u32 s_lane = lane & (SUB - 1), w_sub = lane / SUB;   // packet and worker-within-load of this lane
     const u32 grp_end = (u32)((hi + SUB - 1) / SUB);
     u32 accepted = 0;
+    double sq = 0.0;      // change of the sum of squares of the stored values caused by this lane's writes
 
     for (u32 grp = (u32)(lo / SUB) + blockIdx.x; grp < grp_end; grp += gridDim.x) {
         const u32 seq0 = grp * SUB;
@@ -542,7 +548,10 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
                         const u32 i4 = 4 * u + c;
                         if (i4 >= 2 && i4 - 2 < len) {
                             float* d = dst0 + i4;
-                            *d = rmw ? (*d + q[c]) : q[c];
+                            float nv = q[c] * inv_w;
+                            if (rmw) { const float o = *d; sq -= (double)o * (double)o; nv = o + nv; }
+                            *d = nv;
+                            sq += (double)nv * (double)nv;
                         }
                     }
                 }
@@ -550,13 +559,16 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
         }
         __syncthreads();                                     // LDS is reused by the next group
     }
-    // accepted packets of this block: one plain add to the block's own row (no shared atomics)
-    if (lane == 0) sh_new[wave] = accepted;
+    // accepted packets and sum-of-squares change of this block: plain adds to the block's own rows
+    // (no shared atomics; kernels on the stream run one after the other)
+    sq = wave_sum_f64(sq);
+    if (lane == 0) { sh_new[wave] = accepted; sh_sq[wave] = sq; }
     __syncthreads();
     if (threadIdx.x == 0) {
         u32 total = 0;
-        for (int i = 0; i < GA_WAVES; ++i) total += sh_new[i];
-        if (total) accept_rows[blockIdx.x] += total;
+        double t = 0.0;
+        for (int i = 0; i < GA_WAVES; ++i) { total += sh_new[i]; t += sh_sq[i]; }
+        if (total) { accept_rows[blockIdx.x] += total; sumsq_rows[blockIdx.x] += t; }
     }
 }
 
@@ -615,9 +627,10 @@ template <int NP>
 __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_staged(
     Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
     float* acc0, float* acc1, uint8_t* __restrict__ home, u32 pick,
-    const u64* __restrict__ counters, u64* __restrict__ accept_rows, u32 sub, u32 sub_log2, u32 n_pass,
-    u32 table_in_lds) {
+    const u64* __restrict__ counters, u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows, float inv_w,
+    u32 sub, u32 sub_log2, u32 n_pass, u32 table_in_lds) {
     extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, slots, bucket table
+    __shared__ double sh_sq[GS_READERS];
     __shared__ u64 sh_elem[2][SUB];
     __shared__ u32 sh_len[2][SUB];
     __shared__ u32 sh_home[2][SUB];                 // accumulator copy each packet of the group goes to
@@ -650,6 +663,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
     const u32 grp_end = (u32)((hi + sub - 1) >> sub_log2);
     const u32 n_it = grp0 < grp_end ? (grp_end - grp0 + gridDim.x - 1) / gridDim.x : 0;
     u32 accepted = 0;
+    double sq = 0.0;      // change of the sum of squares of the stored values caused by this lane's packets
 
     for (u32 it = 0; it <= n_it; ++it) {            // one extra turn so the writer drains the last group
         const u32 cur = it & 1;
@@ -747,18 +761,21 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                     for (int q = 0; q < (NP > 0 ? NP : 1); ++q) {
                         const u32 u = q * WAVE + lane;
                         if (u >= units) continue;
-                        float4 r = a[q];
-                        if (rmw) {                                // result = old value + this batch's sum
-                            const float* o = acc + sh_elem[cur][t] - 2 + 4 * u;   // packet float position 4u+c -> o[c]
-                            float qv[4] = {r.x, r.y, r.z, r.w};
-                            #pragma unroll
-                            for (int c = 0; c < 4; ++c) {
-                                const u32 i4 = 4 * u + c;
-                                if (i4 >= 2 && i4 - 2 < len) qv[c] = o[c] + qv[c];
+                        float qv[4] = {a[q].x * inv_w, a[q].y * inv_w, a[q].z * inv_w, a[q].w * inv_w};
+                        const float* o = acc + sh_elem[cur][t] - 2 + 4 * u;       // packet float position 4u+c -> o[c]
+                        #pragma unroll
+                        for (int c = 0; c < 4; ++c) {
+                            const u32 i4 = 4 * u + c;
+                            if (i4 >= 2 && i4 - 2 < len) {
+                                if (rmw) {                        // result = old value + this batch's sum
+                                    const float ov = o[c];
+                                    sq -= (double)ov * (double)ov;
+                                    qv[c] = ov + qv[c];
+                                }
+                                sq += (double)qv[c] * (double)qv[c];
                             }
-                            r = make_float4(qv[0], qv[1], qv[2], qv[3]);
                         }
-                        dstbuf[t * upp + u] = r;
+                        dstbuf[t * upp + u] = make_float4(qv[0], qv[1], qv[2], qv[3]);
                     }
                 }
             } else {
@@ -779,30 +796,37 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                 if (rmw) h = home[seq0 + t];
                 else if (lane == 0) home[seq0 + t] = (uint8_t)pick;
                 if (lane == 0) sh_home[cur][t] = h;
-                if (active && rmw) {
-                    // earlier batches already wrote this span: result = old value + this batch's sum
+                if (active) {
                     const float* o = (h ? acc1 : acc0) + sh_elem[cur][t] - 2 + 4 * u;   // packet float position 4u+c -> o[c]
-                    float q[4] = {a.x, a.y, a.z, a.w};
+                    float q[4] = {a.x * inv_w, a.y * inv_w, a.z * inv_w, a.w * inv_w};
                     #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const u32 i4 = 4 * u + c;
-                        if (i4 >= 2 && i4 - 2 < len) q[c] = o[c] + q[c];
+                        if (i4 >= 2 && i4 - 2 < len) {
+                            if (rmw) {      // earlier batches already wrote this span: result = old value + this batch's sum
+                                const float ov = o[c];
+                                sq -= (double)ov * (double)ov;
+                                q[c] = ov + q[c];
+                            }
+                            sq += (double)q[c] * (double)q[c];
+                        }
                     }
-                    a = make_float4(q[0], q[1], q[2], q[3]);
+                    dstbuf[t * upp + u] = make_float4(q[0], q[1], q[2], q[3]);
                 }
-                if (active) dstbuf[t * upp + u] = a;
             }
             }
         }
         __syncthreads();
     }
-    // accepted packets of this block: one plain add to the block's own row (no shared atomics)
-    if (wave < n_readers && lane == 0) sh_new[wave] = accepted;
+    // accepted packets and sum-of-squares change of this block: plain adds to the block's own rows
+    sq = wave_sum_f64(sq);
+    if (wave < n_readers && lane == 0) { sh_new[wave] = accepted; sh_sq[wave] = sq; }
     __syncthreads();
     if (threadIdx.x == 0) {
         u32 total = 0;
-        for (u32 i = 0; i < n_readers; ++i) total += sh_new[i];
-        if (total) accept_rows[blockIdx.x] += total;
+        double t = 0.0;
+        for (u32 i = 0; i < n_readers; ++i) { total += sh_new[i]; t += sh_sq[i]; }
+        if (total) { accept_rows[blockIdx.x] += total; sumsq_rows[blockIdx.x] += t; }
     }
 }
 
@@ -909,34 +933,53 @@ __device__ __forceinline__ u32 div_small(u32 x, u32 P, float inv_p) {
     return t;
 }
 
-__device__ __forceinline__ float scale_mean(float v, float inv_w, int use_div, float wf) {
-    return use_div ? v / wf : v * inv_w;
-}
-
-// out = acc / W where some worker delivered the packet, 0 elsewhere; per-block sum of out^2.
+// Compensation pass (Alg. "DBLP_RECV" last statements, Alg. "Server" mean).  Per packet span:
+//   some worker delivered it   out = src            (scale_mode 0: the gather already divided by W)
+//                              out = src / W        (scale_mode 1: W is not a power of two)
+//                              where src is the accumulator copy that home[seq] names;
+//                              nothing at all when src and out are the same memory and there is
+//                              no scaling (in-place form: only moved and missing spans are touched)
+//   nobody delivered it        out = 0 exactly
 // A tile of 8 packets inside one bucket is one contiguous element range: it is walked in
-// 16-byte aligned chunks (float4 load, scale, float4 store); chunks that straddle a packet or
-// the range's ends, and tiles that cross a bucket boundary, go element by element.
-// home[seq] (padded to a multiple of 8 entries) names the accumulator copy that holds the packet's span.
+// 16-byte aligned chunks (float4 load, store); chunks that straddle a packet or the range's
+// ends, and tiles that cross a bucket boundary, go element by element.
+// home[seq] (padded to a multiple of 8 entries) names the copy that holds the packet's span; with
+// move_home set (in-place form) the entries of moved spans are reset to copy 0.
+// With scale_mode 1 the per-block sums of out^2 go to partials[blockIdx.x].  Otherwise the sum of
+// squares is already known: the gather kernels kept it per block in sumsq_rows, and the one extra
+// block of this launch (blockIdx.x == n_work_blocks) adds those rows up in a fixed order and
+// writes the total to the host mailbox.
 template <bool TABLE_IN_LDS>
-__global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restrict__ bitmap, const float* acc0,
-                                                     const float* acc1, const uint8_t* __restrict__ home,
-                                                     float* __restrict__ out, float inv_w, int use_div, float wf,
-                                                     double* __restrict__ partials) {
+__global__ __launch_bounds__(256) void finalize_pass(Geo g, const u64* __restrict__ bitmap, const float* acc0,
+                                                     const float* acc1, uint8_t* __restrict__ home,
+                                                     float* out, int scale_mode, float wf, int move_home,
+                                                     double* __restrict__ partials, u32 n_work_blocks,
+                                                     const double* __restrict__ sumsq_rows, u32 n_rows,
+                                                     double* __restrict__ mailbox) {
     __shared__ double wsum[4];
     extern __shared__ u32 fs_lds[];             // bucket boundaries (B + 1 words) when TABLE_IN_LDS
+    const u32 lane = lane_id();
+    const u32 wave_in_block = threadIdx.x / WAVE;
+    if (blockIdx.x >= n_work_blocks) {          // the extra block: fixed-order sum of the gather's rows
+        double s = 0.0;
+        for (u32 i = threadIdx.x; i < n_rows; i += 256) s += sumsq_rows[i];
+        s = wave_sum_f64(s);
+        if (lane == 0) wsum[wave_in_block] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) mailbox[0] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+        return;
+    }
     const u32* fs = g.first_seq;
     if (TABLE_IN_LDS) {
         for (u32 i = threadIdx.x; i <= g.B; i += blockDim.x) fs_lds[i] = g.first_seq[i];
         __syncthreads();
         fs = fs_lds;
     }
-    const u32 lane = lane_id();
-    const u32 wave_in_block = threadIdx.x / WAVE;
     const u32 wave = blockIdx.x * (blockDim.x / WAVE) + wave_in_block;
-    const u32 n_waves = gridDim.x * (blockDim.x / WAVE);
+    const u32 n_waves = n_work_blocks * (blockDim.x / WAVE);
     const u32 n_tiles = (g.n_pkts + FIN_TILE - 1) / FIN_TILE;
     const float inv_p = 1.0f / (float)g.P;
+    const bool skip_same = scale_mode == 0;     // a span that already sits in `out` needs no copy
     double dsum = 0.0;
     for (u32 tile = wave; tile < n_tiles; tile += n_waves) {
         const u32 seq0 = tile * FIN_TILE;
@@ -947,6 +990,14 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
         u64 any = ((u64)wave_reduce<OpOr>((u32)(mine >> 32)) << 32) | wave_reduce<OpOr>((u32)mine);
         any >>= (seq0 & 63);
         const u64 hm = *(const u64*)(home + seq0);          // byte t = copy of packet seq0 + t (valid where `any` has bit t)
+        // which of the tile's packets need work at all (wave-uniform)
+        u32 todo = 0;
+        for (u32 t = 0; t < n_t; ++t) {
+            const bool got = (any >> t) & 1ull;
+            const float* src = ((hm >> (8 * t)) & 1ull) ? acc1 : acc0;
+            if (!got || !(skip_same && src == out)) todo |= 1u << t;
+        }
+        if (!todo) continue;
         u32 b = find_bucket(fs, g.B, seq0);
         if (seq0 + n_t <= fs[b + 1]) {
             const u64 elem0 = g.b_off[b] + (u64)(seq0 - fs[b]) * g.P;
@@ -958,21 +1009,24 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
                 const u64 lo_e = e0 > elem0 ? e0 : elem0, hi_e = e0 + 3 < end - 1 ? e0 + 3 : end - 1;
                 const u32 t_lo = div_small((u32)(lo_e - elem0), g.P, inv_p), t_hi = div_small((u32)(hi_e - elem0), g.P, inv_p);
                 if (e0 >= elem0 && e0 + 4 <= end && t_lo == t_hi) {
+                    if (!((todo >> t_lo) & 1u)) continue;
                     float4 v = make_float4(0.f, 0.f, 0.f, 0.f);      // never received: exactly zero
                     if ((any >> t_lo) & 1ull) {
                         v = *(const float4*)((((hm >> (8 * t_lo)) & 1ull) ? acc1 : acc0) + e0);
-                        v.x = scale_mean(v.x, inv_w, use_div, wf); v.y = scale_mean(v.y, inv_w, use_div, wf);
-                        v.z = scale_mean(v.z, inv_w, use_div, wf); v.w = scale_mean(v.w, inv_w, use_div, wf);
-                        dsum += (double)((v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w));
+                        if (scale_mode) {
+                            v.x = v.x / wf; v.y = v.y / wf; v.z = v.z / wf; v.w = v.w / wf;
+                            dsum += (double)((v.x * v.x + v.y * v.y) + (v.z * v.z + v.w * v.w));
+                        }
                     }
                     *(float4*)(out + e0) = v;
                 } else {
                     for (u64 e = lo_e; e <= hi_e; ++e) {
-                        float v = 0.f;
                         const u32 t_e = div_small((u32)(e - elem0), g.P, inv_p);
+                        if (!((todo >> t_e) & 1u)) continue;
+                        float v = 0.f;
                         if ((any >> t_e) & 1ull) {
-                            v = scale_mean((((hm >> (8 * t_e)) & 1ull) ? acc1 : acc0)[e], inv_w, use_div, wf);
-                            dsum += (double)(v * v);
+                            v = (((hm >> (8 * t_e)) & 1ull) ? acc1 : acc0)[e];
+                            if (scale_mode) { v = v / wf; dsum += (double)(v * v); }
                         }
                         out[e] = v;
                     }
@@ -982,15 +1036,16 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
             for (u32 t = 0; t < n_t; ++t) {
                 const u32 seq = seq0 + t;
                 while (seq >= fs[b + 1]) ++b;
+                if (!((todo >> t) & 1u)) continue;
                 u64 elem; u32 len;
                 packet_span(g, seq, b, &elem, &len);
                 float s = 0.f;
                 if ((any >> t) & 1ull) {
                     const float* acc = ((hm >> (8 * t)) & 1ull) ? acc1 : acc0;
                     for (u32 j = lane; j < len; j += WAVE) {
-                        const float v = scale_mean(acc[elem + j], inv_w, use_div, wf);
+                        float v = acc[elem + j];
+                        if (scale_mode) { v = v / wf; s += v * v; }
                         out[elem + j] = v;
-                        s += v * v;
                     }
                 } else {
                     for (u32 j = lane; j < len; j += WAVE) out[elem + j] = 0.f;
@@ -998,11 +1053,15 @@ __global__ __launch_bounds__(256) void finalize_mean(Geo g, const u64* __restric
                 dsum += (double)s;
             }
         }
+        // in-place form: the spans that were moved now live in copy 0
+        if (move_home && lane < n_t && ((any >> lane) & 1ull) && ((hm >> (8 * lane)) & 1ull)) home[seq0 + lane] = 0;
     }
-    dsum = wave_sum_f64(dsum);
-    if (lane == 0) wsum[wave_in_block] = dsum;
-    __syncthreads();
-    if (threadIdx.x == 0) partials[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    if (scale_mode) {
+        dsum = wave_sum_f64(dsum);
+        if (lane == 0) wsum[wave_in_block] = dsum;
+        __syncthreads();
+        if (threadIdx.x == 0) partials[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+    }
 }
 
 // Sum of squares of a plain vector (16-byte aligned), same partials layout.
@@ -1082,7 +1141,6 @@ __global__ __launch_bounds__(256) void classify_rw(const uint8_t* __restrict__ s
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-#define DBLP_LATE_TRIES 3      // attempts to find a second accumulator copy after set-up
 struct dblp_ctx {
     Geo g;
     u64 N;
@@ -1097,14 +1155,15 @@ struct dblp_ctx {
     // allocation ends with CLS_SCRATCH_BYTES that classify_rw may overwrite
     void* acc_alloc[2]; float* d_acc[2]; float* d_scratch[2];
     int n_acc;              // 1 or 2
+    int acc_caller;         // the copies are the caller's buffers: never measured, never freed
     int acc_distinct;       // the two copies were measured to lie in different thirds of HBM
     float place_ms[2];      // that measurement: probe time writing to copy 0 / copy 1 (0 = not taken)
     int place_steps;        // candidates tried by the placement search
-    int want_second;        // a second copy was asked for with placement and not found
-    int late_left;          // attempts left to find it later, against a caller's buffer
-    int late_used;          // attempts made
-    float t_min;            // fastest probe time per sample seen so far against the first copy
-    void* late_held[2 * DBLP_LATE_TRIES]; int n_late_held;   // rejected late candidates, kept while attempts remain
+    double place_seconds;   // time the search took
+    double search_fraction; // share of the free memory the search may hold
+    double search_seconds;  // its time limit
+    int fold;               // W is a power of two: the gather stores sum / W
+    int norm_in_mailbox;    // the last finalize left the sum of squares in the host mailbox
     int acc_policy;         // DBLP_ACC_*
     int last_pick;          // copy the last batch wrote new spans to
     u32 batch_no;
@@ -1115,6 +1174,7 @@ struct dblp_ctx {
     u32* d_need; u32* d_missing; u64* d_offs; double* d_partials;
     u32* d_block_tallies;   // [IDX_BLOCKS_PER_CU * n_cus][5], written by index_arrivals
     u64* d_accept_rows;     // [2][ACCEPT_ROWS] accepted packets per gather block (staged grid, direct grid)
+    double* d_sumsq_rows;   // [2][ACCEPT_ROWS] sum of squares of what each gather block stored (same allocation)
     u64* h_mailbox;         // pinned host memory, 8 x u64, also mapped into the device
     u64* d_mailbox;         // device address of h_mailbox
     // host copies of the geometry
@@ -1130,11 +1190,6 @@ struct dblp_ctx {
     std::vector<hipEvent_t>* ev_pool; // free events
     char err[256];
 };
-
-static void release_late_held(dblp_ctx* c) {
-    for (int i = 0; i < c->n_late_held; ++i) (void)hipFree(c->late_held[i]);
-    c->n_late_held = 0;
-}
 
 static hipEvent_t prof_event(dblp_ctx* c) {
     hipEvent_t e = nullptr;
@@ -1193,11 +1248,10 @@ extern "C" int dblp_destroy(dblp_ctx* c) {
     if (!c) return DBLP_OK;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->stream);
-    void* dev[] = {c->d_first_seq, c->d_b_off, c->d_b_cnt, c->d_bitmap, c->d_pending, c->acc_alloc[0], c->acc_alloc[1],
-                   c->d_home, c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials, c->d_block_tallies,
+    void* dev[] = {c->d_first_seq, c->d_b_off, c->d_b_cnt, c->d_bitmap, c->d_pending,
+                   c->acc_caller ? nullptr : c->acc_alloc[0], c->acc_caller ? nullptr : c->acc_alloc[1], c->d_home, c->d_counters, c->d_need, c->d_missing, c->d_offs, c->d_partials, c->d_block_tallies,
                    c->d_accept_rows};
     for (void* p : dev) if (p) (void)hipFree(p);
-    release_late_held(c);
     for (hipEvent_t e : c->cls_ev) if (e) (void)hipEventDestroy(e);
     if (c->h_mailbox) (void)hipHostFree(c->h_mailbox);
     if (c->timed) { for (auto& t : *c->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); } delete c->timed; }
@@ -1224,17 +1278,23 @@ static float time_rw(dblp_ctx* c, const void* src, float* scratch) {
     return best;
 }
 
-// (Re)allocates the accumulator as `copies` copies.  place != 0: search for a second copy in
-// another third of the HBM address space than the first, and have no second copy if none is found.
+// (Re)allocates the library-owned accumulator as `copies` copies.  place != 0: search for a second
+// copy in another third of the HBM address space than the first, within the context's limits
+// (share of the free memory held at once, seconds), and have no second copy if none is found.
 // The contents of the round in progress are lost.
 #define PLACE_MAX_STEPS 40
 #define PLACE_STRIDE_BYTES (6ull << 30)
+static double wall_seconds() {
+    struct timespec ts;
+    clock_gettime(CLOCK_MONOTONIC, &ts);
+    return (double)ts.tv_sec + 1e-9 * (double)ts.tv_nsec;
+}
+
 static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, DBLP_EHIP, "accumulator_copies: synchronize");
     for (int i = 0; i < 2; ++i) { if (c->acc_alloc[i]) (void)hipFree(c->acc_alloc[i]); c->acc_alloc[i] = nullptr; }
-    release_late_held(c);
-    c->n_acc = 1; c->acc_distinct = 0; c->place_ms[0] = c->place_ms[1] = 0.f; c->place_steps = 0;
-    c->want_second = 0; c->late_left = 0; c->late_used = 0; c->t_min = 0.f; c->n_picked = 0; c->last_pick = 0; c->round_open = 0; c->finalized = 0;
+    c->n_acc = 1; c->acc_distinct = 0; c->place_ms[0] = c->place_ms[1] = 0.f; c->place_steps = 0; c->place_seconds = 0.0;
+    c->n_picked = 0; c->last_pick = 0; c->round_open = 0; c->finalized = 0; c->norm_in_mailbox = 0;
     const size_t bytes = (c->N * sizeof(float) + 255) / 256 * 256;     // the scratch area starts aligned
     const size_t scratch = copies == 2 ? CLS_SCRATCH_BYTES : 0;
     if (hipMalloc(&c->acc_alloc[0], bytes + scratch) != hipSuccess) { (void)hipGetLastError(); return fail(c, DBLP_ENOMEM, "accumulator"); }
@@ -1250,27 +1310,26 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
         if (hipMalloc(&p, bytes + scratch) == hipSuccess) adopt(p); else (void)hipGetLastError();
         return DBLP_OK;
     }
-    if (place == 2) {        // no search now: only the later attempts against the caller's buffers
-        c->want_second = 1; c->late_left = DBLP_LATE_TRIES;
-        return DBLP_OK;
-    }
     // Walk through the free memory: candidate, then a holder allocation that pushes the next
     // candidate further on, until a candidate measures differently from the first copy against
-    // the same read buffer or nine tenths of the memory are held.
-    // what the probe reads: a buffer allocated right after the first copy (next to its end, where
-    // the scratch area that the reference measurement writes lies)
+    // the same read buffer, or the share of the free memory that may be held is reached, or time
+    // is up.  What the probe reads: a buffer allocated right after the first copy (next to its
+    // end, where the scratch area that the reference measurement writes lies).
+    const double t_start = wall_seconds();
     void* near0 = nullptr;
     if (hipMalloc(&near0, CLS_SAMPLE_BYTES) != hipSuccess) { (void)hipGetLastError(); return DBLP_OK; }
     const void* rd = near0;
     size_t free_b = 0, total_b = 0;
-    if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); total_b = 0; }
+    if (hipMemGetInfo(&free_b, &total_b) != hipSuccess) { (void)hipGetLastError(); free_b = 0; }
+    const size_t may_hold = (size_t)((double)free_b * c->search_fraction);
     const float t_ref = time_rw(c, rd, c->d_scratch[0]);
     c->place_ms[0] = t_ref > 0.f ? t_ref : 0.f;
-    float t_fastest = t_ref > 0.f ? t_ref : 0.f;          // of the probe times seen in this search
     void* held[2 * PLACE_MAX_STEPS];
     int n_held = 0;
     size_t held_bytes = 0;
-    for (int step = 0; step < PLACE_MAX_STEPS && t_ref > 0.f && held_bytes < total_b / 10 * 9; ++step) {
+    for (int step = 0; step < PLACE_MAX_STEPS && t_ref > 0.f; ++step) {
+        if (held_bytes + bytes + scratch > may_hold) break;
+        if (wall_seconds() - t_start > c->search_seconds) break;
         void* cand = nullptr;
         if (hipMalloc(&cand, bytes + scratch) != hipSuccess) { (void)hipGetLastError(); break; }
         // both ends of the candidate must differ from the first copy, and in the same direction
@@ -1280,31 +1339,34 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
         auto differs = [&](float t) { const float hi = t > t_ref ? t : t_ref; return t > 0.f && fabsf(t - t_ref) > 0.07f * hi; };
         c->place_ms[1] = t_end > 0.f ? t_end : 0.f;
         c->place_steps = step + 1;
-        if (t_end > 0.f && t_end < t_fastest) t_fastest = t_end;
         if (differs(t_end) && differs(t_beg) && (t_end < t_ref) == (t_beg < t_ref)) { adopt(cand); c->acc_distinct = 1; break; }
         held[n_held++] = cand; held_bytes += bytes + scratch;
+        if (held_bytes + PLACE_STRIDE_BYTES > may_hold) break;
         void* holder = nullptr;
         if (hipMalloc(&holder, PLACE_STRIDE_BYTES) != hipSuccess) { (void)hipGetLastError(); break; }
         held[n_held++] = holder; held_bytes += PLACE_STRIDE_BYTES;
     }
     for (int i = 0; i < n_held; ++i) (void)hipFree(held[i]);
-    if (near0) (void)hipFree(near0);
-    if (c->n_acc < 2) { c->want_second = 1; c->late_left = DBLP_LATE_TRIES; c->t_min = t_fastest; }
+    (void)hipFree(near0);
     (void)hipGetLastError();
+    c->place_seconds = wall_seconds() - t_start;
     return DBLP_OK;
 }
 
-// Which copy the spans that this batch writes first should go to.
+// Which copy the spans that this batch writes first should go to.  Never allocates.  Measures
+// (and then waits for its probe kernel) only under the automatic policy on a context with two
+// library-owned copies, once per large packet buffer.
 static int pick_copy(dblp_ctx* c, const void* d_packets, u64 bytes, u64 n_slots, u64 n_arrivals) {
-    if (c->n_acc < 2 && !(c->want_second && c->late_left > 0)) return 0;
+    if (c->n_acc < 2) return 0;
     switch (c->acc_policy) {
     case DBLP_ACC_FIRST: return 0;
-    case DBLP_ACC_SECOND: return c->n_acc == 2 ? 1 : 0;
-    case DBLP_ACC_ALTERNATE: return c->n_acc == 2 ? (int)(c->batch_no & 1u) : 0;
+    case DBLP_ACC_SECOND: return 1;
+    case DBLP_ACC_ALTERNATE: return (int)(c->batch_no & 1u);
     default: break;
     }
-    // automatic: measure the buffer once; small or thinly used buffers are not worth it
-    if (bytes < CLS_SAMPLE_BYTES || n_arrivals < n_slots / 8) return 0;
+    // automatic: measure the buffer once; small or thinly used buffers are not worth it, and
+    // caller-owned copies have no scratch area to write to
+    if (c->acc_caller || bytes < CLS_SAMPLE_BYTES || n_arrivals < n_slots / 8) return 0;
     for (u32 i = 0; i < c->n_picked; ++i)
         if (c->picked[i].p == d_packets && c->picked[i].bytes == bytes) return c->picked[i].pick;
     const u64 last = (bytes - CLS_SAMPLE_BYTES) & ~15ull;
@@ -1321,43 +1383,8 @@ static int pick_copy(dblp_ctx* c, const void* d_packets, u64 bytes, u64 n_slots,
     };
     const float t0 = measure(c->d_scratch[0]);
     if (t0 < 0.f) return 0;
-    int pick = 0;
-    if (c->n_acc == 2) {
-        const float t1 = measure(c->d_scratch[1]);
-        pick = t1 > 0.f && t1 < 0.97f * t0 ? 1 : 0;
-    } else {
-        // No second copy yet (the search at set-up found none).  This buffer is clearly slower
-        // against the first copy than some other measurement was: try once more, now that the
-        // caller's buffers occupy the memory, with a fresh allocation measured against this very
-        // buffer at both of its ends.  At most DBLP_LATE_TRIES such attempts per set-up.
-        const float per_sample = t0 / (float)n_offs;
-        if (c->t_min <= 0.f || per_sample < c->t_min) c->t_min = per_sample;
-        if (per_sample > 1.06f * c->t_min) {
-            --c->late_left; ++c->late_used;
-            const size_t acc_bytes = (c->N * sizeof(float) + 255) / 256 * 256;
-            void* cand = nullptr;
-            if (hipMalloc(&cand, acc_bytes + CLS_SCRATCH_BYTES) == hipSuccess) {
-                const float t_end = measure((float*)((uint8_t*)cand + acc_bytes));
-                const float t_beg = acc_bytes >= CLS_SCRATCH_BYTES ? measure((float*)cand) : t_end;
-                if (t_end > 0.f && t_beg > 0.f && t_end < 0.95f * t0 && t_beg < 0.95f * t0) {
-                    c->acc_alloc[1] = cand; c->n_acc = 2; c->acc_distinct = 1; c->want_second = 0;
-                    c->d_acc[1] = (float*)cand; c->d_scratch[1] = (float*)((uint8_t*)cand + acc_bytes);
-                    c->n_picked = 0;                      // earlier answers were given without a second copy
-                    pick = 1;
-                } else {
-                    // keep it (and a holder behind it) until the attempts are over, so that the
-                    // next attempt gets memory from somewhere else
-                    c->late_held[c->n_late_held++] = cand;
-                    void* holder = nullptr;
-                    if (hipMalloc(&holder, PLACE_STRIDE_BYTES) == hipSuccess) c->late_held[c->n_late_held++] = holder;
-                    else (void)hipGetLastError();
-                }
-            } else {
-                (void)hipGetLastError();
-            }
-            if (c->n_acc == 2 || c->late_left == 0) release_late_held(c);
-        }
-    }
+    const float t1 = measure(c->d_scratch[1]);
+    const int pick = t1 > 0.f && t1 < 0.97f * t0 ? 1 : 0;
     dblp_ctx::Picked& slot = c->picked[c->n_picked < 32 ? c->n_picked++ : c->batch_no % 32];
     slot.p = d_packets; slot.bytes = bytes; slot.pick = pick;
     return pick;
@@ -1380,6 +1407,14 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     if (cfg->payload_floats == 0 || cfg->payload_floats > 65535) return DBLP_EINVAL;
     if (cfg->n_buckets == 0 || cfg->n_elems == 0) return DBLP_EINVAL;
     if (!(cfg->eta >= 0.0)) return DBLP_EINVAL;
+    if (cfg->accumulator_mode < DBLP_ACCMODE_SINGLE || cfg->accumulator_mode > DBLP_ACCMODE_SEARCH) return DBLP_EINVAL;
+    if (cfg->search_free_fraction < 0.0 || cfg->search_free_fraction > 0.9 || !(cfg->search_seconds >= 0.0)) return DBLP_EINVAL;
+    for (int i = 0; i < 2; ++i)
+        if (cfg->d_accumulator[i] && ((uintptr_t)cfg->d_accumulator[i] & 255) != 0) return DBLP_EINVAL;
+    if (cfg->d_accumulator[1] && (!cfg->d_accumulator[0] || cfg->accumulator_mode != DBLP_ACCMODE_PAIR ||
+                                  cfg->d_accumulator[1] == cfg->d_accumulator[0])) return DBLP_EINVAL;
+    if (cfg->d_accumulator[0] && cfg->accumulator_mode == DBLP_ACCMODE_SEARCH) return DBLP_EINVAL;   // the search owns both copies
+    if (cfg->d_accumulator[0] && cfg->accumulator_mode == DBLP_ACCMODE_PAIR && !cfg->d_accumulator[1]) return DBLP_EINVAL;
     const u32 B = cfg->n_buckets, P = cfg->payload_floats;
     u64 expect = 0, n_pkts = 0;
     for (u32 b = 0; b < B; ++b) {
@@ -1394,6 +1429,9 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     dblp_ctx* c = (dblp_ctx*)calloc(1, sizeof *c);
     if (!c) return DBLP_ENOMEM;
     c->N = cfg->n_elems; c->eta = cfg->eta; c->device = cfg->device; c->stream = (hipStream_t)cfg->stream;
+    c->search_fraction = cfg->search_free_fraction > 0.0 ? cfg->search_free_fraction : 0.5;
+    c->search_seconds = cfg->search_seconds > 0.0 ? cfg->search_seconds : 2.0;
+    c->fold = (cfg->n_workers & (cfg->n_workers - 1)) == 0;
     c->timed = new (std::nothrow) std::vector<dblp_ctx::Timed>();
     c->ev_pool = new (std::nothrow) std::vector<hipEvent_t>();
     if (!c->timed || !c->ev_pool) { dblp_destroy(c); return DBLP_ENOMEM; }
@@ -1438,7 +1476,7 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     ok = ok && hipMalloc(&c->d_missing, pairs * sizeof(u32)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_offs, pairs * sizeof(u64)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_partials, max_partials * sizeof(double)) == hipSuccess;
-    ok = ok && hipMalloc(&c->d_accept_rows, 2 * ACCEPT_ROWS * sizeof(u64)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_accept_rows, 4 * ACCEPT_ROWS * sizeof(u64)) == hipSuccess;   // + the sum-of-squares rows
     ok = ok && hipMalloc(&c->d_block_tallies, (size_t)c->n_cus * IDX_BLOCKS_PER_CU * 5 * sizeof(u32)) == hipSuccess;
     ok = ok && hipHostMalloc((void**)&c->h_mailbox, 8 * sizeof(u64), hipHostMallocMapped) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); dblp_destroy(c); return DBLP_ENOMEM; }
@@ -1448,6 +1486,7 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     ok = ok && hipMemcpyAsync(c->d_b_cnt, c->h_b_cnt, B * sizeof(u64), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); dblp_destroy(c); return DBLP_EHIP; }
     g.first_seq = c->d_first_seq; g.b_off = c->d_b_off; g.b_cnt = c->d_b_cnt;
+    c->d_sumsq_rows = (double*)(c->d_accept_rows + 2 * ACCEPT_ROWS);
 
     const u64 n_pending = (u64)g.W * n_pkts;
     hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n_pending + 255) / 256, 16)), dim3(256), 0, c->stream,
@@ -1455,14 +1494,24 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (g.W * g.words_pw + 255) / 256, 16)), dim3(256), 0, c->stream,
                        c->d_bitmap, g.W * g.words_pw, 0ull);
     hipLaunchKernelGGL(reset_counters, dim3(1), dim3(64), 0, c->stream, c->d_counters);
-    hipLaunchKernelGGL(fill_u64, dim3(32), dim3(256), 0, c->stream, c->d_accept_rows, (u64)(2 * ACCEPT_ROWS), 0ull);
+    hipLaunchKernelGGL(fill_u64, dim3(32), dim3(256), 0, c->stream, c->d_accept_rows, (u64)(4 * ACCEPT_ROWS), 0ull);
+    hipLaunchKernelGGL(fill_u64, dim3(grid_for(c, (n_pkts + 16 + 2047) / 2048, 16)), dim3(256), 0, c->stream,
+                       (u64*)c->d_home, (u64)((n_pkts + 7) / 8 + 1), 0ull);
     e = hipStreamSynchronize(c->stream);
     if (e != hipSuccess || hipGetLastError() != hipSuccess) { dblp_destroy(c); return DBLP_EHIP; }
-    // accumulator last: a second copy is worth its memory when one round moves enough bytes for a
-    // batch to be measured against the copies
-    const bool big = (u64)g.W * n_pkts * g.stride >= 2 * CLS_SAMPLE_BYTES;
-    const int rc = set_accumulator_copies(c, big ? 2 : 1, big ? 1 : 0);
-    if (rc != DBLP_OK) { dblp_destroy(c); return rc; }
+    // accumulator last
+    if (cfg->d_accumulator[0]) {
+        c->acc_caller = 1;
+        c->acc_alloc[0] = cfg->d_accumulator[0]; c->acc_alloc[1] = cfg->d_accumulator[1];
+        c->d_acc[0] = cfg->d_accumulator[0];
+        c->d_acc[1] = cfg->d_accumulator[1] ? cfg->d_accumulator[1] : cfg->d_accumulator[0];
+        c->n_acc = cfg->d_accumulator[1] ? 2 : 1;
+        c->d_scratch[0] = c->d_scratch[1] = nullptr;
+    } else {
+        const int rc = set_accumulator_copies(c, cfg->accumulator_mode == DBLP_ACCMODE_SINGLE ? 1 : 2,
+                                              cfg->accumulator_mode == DBLP_ACCMODE_SEARCH ? 1 : 0);
+        if (rc != DBLP_OK) { dblp_destroy(c); return rc; }
+    }
     c->err[0] = 0;
     *out = c;
     return DBLP_OK;
@@ -1479,7 +1528,8 @@ extern "C" int dblp_layout(const dblp_ctx* c, uint64_t* n_pkts, uint32_t* stride
 extern "C" int dblp_accumulator_copies(dblp_ctx* c, int copies, int place) {
     if (!c) return DBLP_EINVAL;
     if (copies != 1 && copies != 2) return fail(c, DBLP_EINVAL, "accumulator_copies: 1 or 2");
-    if (place < 0 || place > 2) return fail(c, DBLP_EINVAL, "accumulator_copies: place is 0, 1 or 2");
+    if (place < 0 || place > 1) return fail(c, DBLP_EINVAL, "accumulator_copies: place is 0 or 1");
+    if (c->acc_caller) return fail(c, DBLP_EINVAL, "accumulator_copies: the accumulator is the caller's");
     HIP_TRY(c, hipSetDevice(c->device));
     return set_accumulator_copies(c, copies, place);
 }
@@ -1493,23 +1543,29 @@ extern "C" int dblp_accumulator_policy(dblp_ctx* c, int policy) {
 
 extern "C" int dblp_accumulator_info(const dblp_ctx* c, int* copies, int* distinct, int* last_pick, double* placement_ms) {
     if (!c) return DBLP_EINVAL;
-    if (placement_ms) { placement_ms[0] = c->place_ms[0]; placement_ms[1] = c->place_ms[1]; placement_ms[2] = c->place_steps; placement_ms[3] = c->late_used; }
+    if (placement_ms) { placement_ms[0] = c->place_ms[0]; placement_ms[1] = c->place_ms[1]; placement_ms[2] = c->place_steps; placement_ms[3] = c->place_seconds; }
     if (copies) *copies = c->n_acc;
     if (distinct) *distinct = c->acc_distinct;
     if (last_pick) *last_pick = c->last_pick;
     return DBLP_OK;
 }
 
+extern "C" int dblp_accumulator_ptr(const dblp_ctx* c, int which, float** d_copy) {
+    if (!c || !d_copy) return DBLP_EINVAL;
+    if (which < 0 || which >= c->n_acc || !c->acc_alloc[0]) return DBLP_EINVAL;
+    *d_copy = c->d_acc[which];
+    return DBLP_OK;
+}
+
 extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
     if (!c) return DBLP_EINVAL;
     if (!c->acc_alloc[0]) return fail(c, DBLP_ESTATE, "begin_round: no accumulator (dblp_accumulator_copies ran out of memory)");
-    if (c->n_late_held) { HIP_TRY(c, hipStreamSynchronize(c->stream)); release_late_held(c); }   // not kept across rounds
     HIP_TRY(c, hipSetDevice(c->device));
     const u64 n = c->g.W * c->g.words_pw;
-    hipLaunchKernelGGL(reset_round, dim3(grid_for(c, (n + 2 * ACCEPT_ROWS + 255) / 256, 16)), dim3(256), 0, c->stream,
-                       c->d_bitmap, n, c->d_accept_rows, (u64)(2 * ACCEPT_ROWS), c->d_counters);
+    hipLaunchKernelGGL(reset_round, dim3(grid_for(c, (n + 4 * ACCEPT_ROWS + 255) / 256, 16)), dim3(256), 0, c->stream,
+                       c->d_bitmap, n, c->d_accept_rows, (u64)(4 * ACCEPT_ROWS), c->d_counters);
     LAUNCH_CHECK(c, "begin_round");
-    c->round = round; c->round_open = 1; c->finalized = 0;
+    c->round = round; c->round_open = 1; c->finalized = 0; c->norm_in_mailbox = 0;
     return DBLP_OK;
 }
 
@@ -1610,6 +1666,7 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
                            (const u64*)d_queue, (u64)n_arrivals, (u32)c->round, c->d_pending, c->d_block_tallies);
         hipLaunchKernelGGL(fold_index_tallies, dim3(1), dim3(256), 0, c->stream, c->d_block_tallies, grid, c->d_counters);
     }
+    const float inv_w = c->fold ? 1.0f / (float)g.W : 1.0f;   // exact for the powers of two it is used with
     {
         ProfScope ps(c, DBLP_K_GATHER);
         u32 sub = SUB, sub_log2 = 4;
@@ -1627,25 +1684,26 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
             if (per_cu > GS_MAX_PER_CU) per_cu = GS_MAX_PER_CU;
             if (per_cu < 1) per_cu = 1;
-            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u64*, u64*, u32, u32, u32, u32) =
+            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u64*, u64*, double*, float, u32, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
             hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, per_cu)), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
-                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows, sub, sub_log2, n_pass,
-                               table_in_lds);
+                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows, c->d_sumsq_rows, inv_w,
+                               sub, sub_log2, n_pass, table_in_lds);
         }
         {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
             const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
             hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
-                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows + ACCEPT_ROWS, sub >= 2 ? 1 : 0);
+                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows + ACCEPT_ROWS,
+                               c->d_sumsq_rows + ACCEPT_ROWS, inv_w, sub >= 2 ? 1 : 0);
         }
     }
     LAUNCH_CHECK(c, "apply_arrivals");
-    c->finalized = 0;
+    c->finalized = 0; c->norm_in_mailbox = 0;
     return DBLP_OK;
 }
 
@@ -1705,27 +1763,30 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
     if (!c) return DBLP_EINVAL;
     if (!c->round_open) return fail(c, DBLP_ESTATE, "finalize before begin_round");
     if (compensation != DBLP_COMP_ZEROFILL_MEAN) return fail(c, DBLP_EINVAL, "finalize: unknown compensation mode");
-    if (!d_out) return fail(c, DBLP_EINVAL, "finalize: null output");
+    const bool in_place = !d_out || d_out == c->d_acc[0];
+    if (in_place && !c->fold) return fail(c, DBLP_EINVAL, "finalize: the in-place form needs a power-of-two worker count");
+    if (!in_place && c->n_acc == 2 && d_out == c->d_acc[1]) return fail(c, DBLP_EINVAL, "finalize: d_out is the second accumulator copy");
     if (((uintptr_t)d_out & 15) != 0) return fail(c, DBLP_EINVAL, "finalize: d_out must be 16-byte aligned");
     HIP_TRY(c, hipSetDevice(c->device));
     const Geo& g = c->g;
-    const u32 W = g.W;
-    const int pow2 = (W & (W - 1)) == 0;
     const u64 tiles = ((u64)g.n_pkts + FIN_TILE - 1) / FIN_TILE;
-    const u32 grid = grid_for(c, (tiles + 3) / 4, FIN_BLOCKS_PER_CU);
+    const u32 work = grid_for(c, (tiles + 3) / 4, FIN_BLOCKS_PER_CU);
+    const u32 grid = work + (c->fold ? 1 : 0);      // folded: one more block sums the gather's rows for Eq. 1
+    float* out = in_place ? c->d_acc[0] : d_out;
     {
         ProfScope ps(c, DBLP_K_FINALIZE);
         const size_t table = ((size_t)g.B + 1) * sizeof(u32);
-        if (table <= IDX_TABLE_LDS_MAX)
-            hipLaunchKernelGGL(finalize_mean<true>, dim3(grid), dim3(256), table, c->stream, g, c->d_bitmap, c->d_acc[0], c->d_acc[1],
-                               c->d_home, d_out, 1.0f / (float)W, !pow2, (float)W, c->d_partials);
-        else
-            hipLaunchKernelGGL(finalize_mean<false>, dim3(grid), dim3(256), 0, c->stream, g, c->d_bitmap, c->d_acc[0], c->d_acc[1],
-                               c->d_home, d_out, 1.0f / (float)W, !pow2, (float)W, c->d_partials);
+        void (*kern)(Geo, const u64*, const float*, const float*, uint8_t*, float*, int, float, int, double*, u32,
+                     const double*, u32, double*) = table <= IDX_TABLE_LDS_MAX ? finalize_pass<true> : finalize_pass<false>;
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(256), table <= IDX_TABLE_LDS_MAX ? table : 0, c->stream, g, c->d_bitmap,
+                           (const float*)c->d_acc[0], (const float*)c->d_acc[1], c->d_home, out, c->fold ? 0 : 1, (float)g.W,
+                           in_place ? 1 : 0, c->d_partials, work, (const double*)c->d_sumsq_rows, (u32)(2 * ACCEPT_ROWS),
+                           (double*)(c->d_mailbox + 1));
     }
     LAUNCH_CHECK(c, "finalize");
-    c->n_partials = grid;
+    c->n_partials = work;
     c->finalized = 1;
+    c->norm_in_mailbox = c->fold;
     return DBLP_OK;
 }
 
@@ -1733,22 +1794,25 @@ extern "C" int dblp_phase_signal(dblp_ctx* c, const float* d_vec, double* h_norm
     if (!c) return DBLP_EINVAL;
     if (!h_norm || !h_rel_delta || !h_critical) return fail(c, DBLP_EINVAL, "phase_signal: null host pointer");
     HIP_TRY(c, hipSetDevice(c->device));
-    u32 n_partials;
     if (d_vec) {
         if (((uintptr_t)d_vec & 15) != 0) return fail(c, DBLP_EINVAL, "phase_signal: d_vec must be 16-byte aligned");
-        n_partials = grid_for(c, (c->N / 4 + 255) / 256, FIN_BLOCKS_PER_CU);
+        const u32 n_partials = grid_for(c, (c->N / 4 + 255) / 256, FIN_BLOCKS_PER_CU);
         hipLaunchKernelGGL(sumsq_vec, dim3(n_partials), dim3(256), 0, c->stream, d_vec, (u64)c->N, c->d_partials);
-        c->finalized = 0;   // the partials no longer belong to a finalize
+        hipLaunchKernelGGL(reduce_partials, dim3(1), dim3(256), 0, c->stream, c->d_partials, n_partials,
+                           (double*)(c->d_mailbox + 1));
+        c->finalized = 0;   // neither the partials nor the mailbox belong to a finalize any more
+        c->norm_in_mailbox = 0;
     } else {
         if (!c->finalized) return fail(c, DBLP_ESTATE, "phase_signal without a finalize in this round");
-        n_partials = c->n_partials;
+        if (!c->norm_in_mailbox)     // W not a power of two: the finalize pass left per-block partial sums
+            hipLaunchKernelGGL(reduce_partials, dim3(1), dim3(256), 0, c->stream, c->d_partials, c->n_partials,
+                               (double*)(c->d_mailbox + 1));
     }
-    hipLaunchKernelGGL(reduce_partials, dim3(1), dim3(256), 0, c->stream, c->d_partials, n_partials,
-                       (double*)(c->d_mailbox + 1));
     LAUNCH_CHECK(c, "phase_signal");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     double ss;
     memcpy(&ss, c->h_mailbox + 1, sizeof ss);
+    if (ss < 0.0) ss = 0.0;     // the running sum of squares can end a rounding error below zero
     const double norm = sqrt(ss);
     if (!c->have_prev || c->prev_norm == 0.0) {
         *h_rel_delta = INFINITY;

@@ -81,10 +81,13 @@ def build_scenario(w: wl.Workload, it: int = 0, place: str | None = None, order:
 class OracleRx:
     """Drives oracle.Oracle on host packets."""
 
-    def __init__(self, sc: Scenario, eta: float = 0.5):
+    def __init__(self, sc: Scenario, eta: float = 0.5, threads: int | None = None):
+        """threads: None = the plain single-threaded walk; otherwise the element-range-parallel walk
+        (same results, used to time the baseline on all cores; 0 = all that OpenMP offers)."""
         import oracle
         L = sc.L
         self.sc = sc
+        self.threads, self.threads_used = threads, 1
         self.o = oracle.Oracle(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, eta)
         self.packets = None
         self.src = None
@@ -102,7 +105,8 @@ class OracleRx:
 
     def apply(self, slot_base, n_slots, mask, order, n_arrivals=None):
         st = self.o.stride
-        self.o.apply_arrivals(self.packets[slot_base * st:], self.src[slot_base:], n_slots, mask, order, n_arrivals)
+        self.threads_used = self.o.apply_arrivals(self.packets[slot_base * st:], self.src[slot_base:], n_slots, mask,
+                                                  order, n_arrivals, threads=self.threads)
 
     def loss_account(self, bound_ppm):
         return self.o.loss_account(bound_ppm)
@@ -189,24 +193,34 @@ class GpuRx:
     """Drives the HIP library on device-resident packets built by its own packetize."""
 
     def __init__(self, sc: Scenario, eta: float = 0.5, queue: bool = False, acc_copies: int = 1, acc_policy: int = 0,
-                 acc_place: int = 0):
+                 acc_place: int = 0, result: str = "copy"):
         """queue=True hands every batch over as a receive queue (dblp_apply_arrivals_queue): the
-        descriptors are built here, on the host, from the same (mask, order, per-slot worker)."""
+        descriptors are built here, on the host, from the same (mask, order, per-slot worker).
+        result: "copy" finalize writes a buffer of the caller's; "in_place" finalize(NULL), the result
+        is read from the library's first accumulator copy; "caller" the accumulator copies are
+        tensors owned here and finalize is given the first of them."""
         import torch
         import paper_2605_01989_amd as dblp
         L = sc.L
-        self.sc, self.torch, self.queue = sc, torch, queue
-        self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, eta)
-        assert (self.agg.n_pkts, self.agg.stride) == (L.n_pkts, L.stride)
-        if acc_copies == 2:      # a plain second accumulator copy, and which copy batches write new spans to
-            self.agg.accumulator_copies(2, place=acc_place)
+        self.sc, self.torch, self.queue, self.result = sc, torch, queue, result
+        self.d_out = torch.empty(L.N, dtype=torch.float32, device="cuda")
+        if result == "caller":
+            self.d_second = torch.empty(L.N, dtype=torch.float32, device="cuda") if acc_copies == 2 else None
+            self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, eta,
+                                       accumulator_mode=1 if acc_copies == 2 else 0,
+                                       d_accumulator=(self.d_out, self.d_second))
             self.agg.accumulator_policy(acc_policy)
+        else:
+            self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, eta)
+            if acc_copies == 2:  # a second accumulator copy, and which copy batches write new spans to
+                self.agg.accumulator_copies(2, place=acc_place)
+                self.agg.accumulator_policy(acc_policy)
+        assert (self.agg.n_pkts, self.agg.stride) == (L.n_pkts, L.stride)
         n_slots = L.W * L.n_pkts
         self.packets = torch.zeros(n_slots * L.stride, dtype=torch.uint8, device="cuda")
         self.src = torch.full((n_slots,), -1, dtype=torch.int16, device="cuda")
         self.d_missing = torch.empty(L.W * L.B, dtype=torch.int32, device="cuda")
         self.d_list = torch.empty(max(n_slots, 1), dtype=torch.int64, device="cuda")
-        self.d_out = torch.empty(L.N, dtype=torch.float32, device="cuda")
         self.d_bitmap = torch.empty(L.W * self.agg.words_pw, dtype=torch.int64, device="cuda")
 
     def packetize_all(self, rnd_id: int | None = None):
@@ -253,7 +267,10 @@ class GpuRx:
         return missing, self.d_list[:n].cpu().numpy().view(np.uint64), count, met
 
     def finalize(self):
-        self.agg.finalize(self.d_out)
+        if self.result == "in_place":
+            self.agg.finalize(None)
+            return self.agg.accumulator_tensor(0).cpu().numpy()
+        self.agg.finalize(self.d_out)        # "caller": d_out is the accumulator, so this is in place too
         return self.d_out.cpu().numpy()
 
     def phase_signal(self):
@@ -287,6 +304,20 @@ def abs_scale(sc: Scenario, received: np.ndarray) -> np.ndarray:
 
 
 FLOAT_TOL = 1e-5   # max relative error of the fp32 aggregate against the fp64 oracle
+
+
+def record_stat(name: str, stats: dict) -> None:
+    """Prints one parity record and, when DBLP_PARITY_STATS names a file, appends it there as a
+    JSON line (the plain element-wise relative error and the count of elements above the
+    tolerance are reported this way, next to the asserted metric)."""
+    import json
+    import os
+    line = json.dumps(dict(case=name, **stats), default=lambda v: v.item() if hasattr(v, "item") else str(v))
+    print(line, flush=True)
+    path = os.environ.get("DBLP_PARITY_STATS")
+    if path:
+        with open(path, "a") as f:
+            f.write(line + "\n")
 
 
 def compare_results(got: dict, ref: dict, sc: Scenario) -> dict:

@@ -3,19 +3,24 @@ every packet of a round resident in HBM (167 GB), chunk-streamed application, sh
 and arrival order, burst loss, a 2 % bound with retransmission rounds; and the 124M-element (W=8)
 and 355M-element (W=16, 4 KB packets, microburst windows) workloads, each applied as one batch.
 
-The oracle cannot run a whole round's payloads in seconds, so it computes sampled outputs one by
-one: for a sample of buckets it is given exactly that bucket's packets, in their original relative
-arrival order, and must reproduce the GPU's per-(worker, bucket) counts, retransmit-list entries,
-bitmap bits and aggregated elements for that bucket (loss accounting and aggregation are
-independent across buckets, so a bucket is an exact sub-problem).  Properties that hold at any size
-cover the rest: total missing = packets - accepted, no spurious stale/invalid/duplicate counts, and
-the norm of the returned gradient."""
+Integer outputs are compared in full: the oracle is shown the 8 header bytes of every slot (its
+header-only sender and receiver, pinned on the CPU against the payload-carrying ones), the same
+masks, arrival orders and retransmission draws, and the whole bitmap, the per-(worker, bucket)
+counts and the retransmit list of every probe and the four counters must be equal bit for bit.
+
+The oracle cannot add a whole round's payloads in seconds, so the floats are compared on sampled
+buckets (at least 64 plus the first two and the last two): for each it is given exactly that
+bucket's packets, in their original relative arrival order, and must reproduce the aggregated
+elements of the bucket (aggregation is independent across buckets, so a bucket is an exact
+sub-problem), together with the bucket's counts, list entries and bitmap bits once more.  The norm
+of the returned gradient is checked against an fp64 reduction of the whole output."""
 import dataclasses
 
 import numpy as np
 import pytest
 
 import workloads as wl
+from harness import record_stat
 
 pytestmark = pytest.mark.gpu
 
@@ -86,9 +91,54 @@ def bucket_subproblem(job, b, probes, bound_ppm):
     scale = sum(rec[wk, pkt] * np.abs(grads[wk].astype(np.float64)) for wk in range(L.W)) / L.W
     zero = scale == 0
     assert np.all(got[zero] == 0.0)
-    rel = (np.abs(got - ref)[~zero] / scale[~zero]).max()
+    err = np.abs(got - ref)
+    rel = (err[~zero] / scale[~zero]).max()
     assert rel <= FLOAT_TOL, f"bucket {b}: float parity {rel:.3e}"
-    return rec, rel
+    nz = ref != 0
+    plain = err[nz] / np.abs(ref[nz])
+    return rec, dict(rel=float(rel), plain_max=float(plain.max()) if nz.any() else 0.0,
+                     plain_above=int((plain > FLOAT_TOL).sum()), n=int(cnt))
+
+
+def integer_outputs_in_full(job, probes, bound_ppm, counters, words):
+    """The whole round on the oracle's header-only receiver: every slot's 8 header bytes, the
+    chunk steps' masks and arrival orders, then the retransmission batches exactly as
+    bench.DeviceJob.step hands them over (every listed packet resent, the drawn loss of the
+    round as a mask over the buffer).  Everything integer must be equal in full."""
+    import oracle
+    w, L = job.w, job.L
+    n_slots = L.W * L.n_pkts
+    o = oracle.Oracle(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5))
+    headers = np.empty(n_slots * 8, dtype=np.uint8)
+    src = np.empty(n_slots, dtype=np.uint16)
+    for wk in range(L.W):
+        o.write_headers(wk, job.rnd_id, 0, L.n_pkts, headers, src, slot_map=job.slot_of[wk])
+    o.begin_round(job.rnd_id)
+    s0 = survive(job, 0)
+    for ci, ch in enumerate(job.chunks):
+        local = (job.slot_of[:, ch["s0"]:ch["s1"]] - np.uint32(ch["base"])).astype(np.uint32)
+        mask = wl.slot_mask_words(s0[:, ch["s0"]:ch["s1"]], local)
+        order = wl.arrival_order(job.order, ch["n"], w.seed, ci)
+        o.apply_arrivals(headers[ch["base"] * 8:], src[ch["base"]:], ch["n"], mask, order, ch["n"],
+                         accumulate=False, stride=8)
+    for rnd, pr in enumerate(probes):
+        missing, lst, count, met = o.loss_account(bound_ppm)
+        assert count == pr["count"] and met == pr["met"], f"probe {rnd}: list length / all-met differ"
+        assert np.array_equal(missing, pr["missing"]), f"probe {rnd}: per-bucket counts differ"
+        assert np.array_equal(lst, pr["list"]), f"probe {rnd}: retransmit list differs"
+        if met:
+            break
+        ws = (lst >> np.uint64(32)).astype(np.int64)
+        ss = (lst & np.uint64(0xFFFFFFFF)).astype(np.int64)
+        slots = job.slot_of[ws, ss].astype(np.uint32)
+        mask = wl.slot_mask_words(survive(job, rnd + 1), job.slot_of) if (rnd + 1) in job.d_survive else None
+        o.apply_arrivals(headers, src, n_slots, mask, slots, slots.size, accumulate=False, stride=8)
+    assert o.counters() == counters, (o.counters(), counters)
+    rec = o.received()
+    gbits = np.unpackbits(words.view(np.uint8), axis=1, bitorder="little")[:, :L.n_pkts]
+    assert np.array_equal(gbits, rec), "bitmap differs"
+    assert not np.unpackbits(words.view(np.uint8), axis=1, bitorder="little")[:, L.n_pkts:].any()
+    return rec
 
 
 # workload, bound of the iteration (cfg3: the tight level of its three-level policy; cfg4: its fixed
@@ -101,7 +151,7 @@ def test_full_size_sampled_buckets_and_global_properties(name, BOUND_PPM, extra)
     import torch
     import bench
     w = wl.workload(name)
-    job = bench.DeviceJob(w, n_masks=1)
+    job = bench.DeviceJob(w, n_masks=1, accumulator=bench.default_accumulator(w))   # as bench.py runs it
     L = job.L
     probes = []
     res = job.step(0, BOUND_PPM, record=probes)
@@ -126,18 +176,26 @@ def test_full_size_sampled_buckets_and_global_properties(name, BOUND_PPM, extra)
     bitmap = torch.empty(L.W * job.agg.words_pw, dtype=torch.int64, device="cuda")
     job.agg.get_bitmap(bitmap)
     words = bitmap.cpu().numpy().view(np.uint64).reshape(L.W, job.agg.words_pw)
+    # --- every integer output, in full, against the header-only oracle
+    rec_all = integer_outputs_in_full(job, probes, BOUND_PPM, counters, words)
+    print(f"{name}: integer outputs equal in full ({len(probes)} probes, {first['count']} list entries)", flush=True)
+    # --- floats on sampled buckets: 64 random ones, the first two, the last two, the named extras
     rng = np.random.default_rng(2605)
-    sample = sorted({0, 1, *extra, L.B - 2, L.B - 1, *rng.integers(1, L.B - 2, size=7).tolist()})
-    worst = 0.0
+    pool = np.arange(2, L.B - 2)
+    sample = sorted({0, 1, *extra, L.B - 2, L.B - 1, *rng.choice(pool, size=min(64, pool.size), replace=False).tolist()})
+    assert len(sample) >= 66
+    agg_stats = dict(rel=0.0, plain_max=0.0, plain_above=0, n=0)
     for b in sample:
-        rec, rel = bucket_subproblem(job, b, probes, BOUND_PPM)
+        rec, st = bucket_subproblem(job, b, probes, BOUND_PPM)
         s0, s1 = int(L.first_seq[b]), int(L.first_seq[b + 1])
-        seqs = np.arange(s0, s1)
-        gbits = (words[:, seqs >> 6] >> (seqs & 63).astype(np.uint64)) & np.uint64(1)
-        assert np.array_equal(gbits.astype(np.uint8), rec), f"bucket {b}: bitmap differs"
-        worst = max(worst, rel)
-    print(f"{name} full size: accumulator={job.agg.accumulator_info()} rounds={res['rounds']} first list={first['count']} accepted={counters['accepted']} "
-          f"sampled buckets={sample} worst float rel={worst:.2e}")
+        assert np.array_equal(rec_all[:, s0:s1], rec), f"bucket {b}: bitmap differs"
+        agg_stats = dict(rel=max(agg_stats["rel"], st["rel"]), plain_max=max(agg_stats["plain_max"], st["plain_max"]),
+                         plain_above=agg_stats["plain_above"] + st["plain_above"], n=agg_stats["n"] + st["n"])
+    record_stat(f"{name}_full_size", dict(accumulator=job.agg.accumulator_info(), rounds=res["rounds"], first_list=first["count"],
+                                          accepted=counters["accepted"], sampled_buckets=len(sample), rel_to_addends=agg_stats["rel"],
+                                          plain_rel_max=agg_stats["plain_max"], plain_rel_above_tol=agg_stats["plain_above"],
+                                          n=agg_stats["n"]))
+    del rec_all
     # --- the other hand-over form (mask + order + per-slot worker table instead of receive queues)
     # must give the same bits: the sum over workers is formed in worker order either way
     first_out = job.d_out.clone()

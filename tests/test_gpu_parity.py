@@ -8,7 +8,7 @@ import pytest
 
 import workloads as wl
 from harness import (FLOAT_TOL, GpuRx, OracleRx, build_scenario, compare_results, definition_mean,
-                     run_iteration)
+                     record_stat, run_iteration)
 
 pytestmark = pytest.mark.gpu
 
@@ -90,17 +90,36 @@ def test_parity_small_and_ragged_receive_queue(W, sizes, P, loss, ppm):
     assert stats["rel_to_addends"] <= FLOAT_TOL
 
 
+@pytest.mark.parametrize("result", ["in_place", "caller"])
+@pytest.mark.parametrize("W,sizes,P,loss,ppm", [c for c in CASES if c[0] & (c[0] - 1) == 0])
+def test_parity_small_and_ragged_in_place(W, sizes, P, loss, ppm, result):
+    """The in-place forms of finalize (power-of-two W): the result is read from the library's first
+    accumulator copy, or the accumulator is a buffer of the caller's that is also given as d_out.
+    Same bits as the copying form."""
+    sc = build_scenario(mk(W, sizes, P, loss))
+    stats, got, ref = run_both(sc, ppm, queue=(result == "caller"), result=result)
+    assert stats["rel_to_addends"] <= FLOAT_TOL
+    g1 = GpuRx(sc); g1.packetize_all()
+    one = run_iteration(g1, sc, ppm)
+    assert np.array_equal(one["out"].view(np.uint32), got["out"].view(np.uint32))
+    assert one["norm"] == got["norm"] and one["counters"] == got["counters"]
+
+
 # ------------------------------------------------------------------------------ two accumulator copies
 TWO_COPY_CASES = [CASES[i] for i in (3, 5, 6, 7, 10, 13, 14, 15)]
 
 
+@pytest.mark.parametrize("result", ["copy", "in_place", "caller"])
 @pytest.mark.parametrize("policy", [2, 3])      # always the second copy; alternate per batch
 @pytest.mark.parametrize("W,sizes,P,loss,ppm", TWO_COPY_CASES)
-def test_two_accumulator_copies_give_the_same_bits(W, sizes, P, loss, ppm, policy):
+def test_two_accumulator_copies_give_the_same_bits(W, sizes, P, loss, ppm, policy, result):
     """Where a span lives must not show in any result: first transmissions and retransmission
-    rounds land in different copies under these policies."""
+    rounds land in different copies under these policies; the in-place forms of finalize move
+    the spans of the second copy into the first."""
+    if result != "copy" and W & (W - 1):
+        pytest.skip("the in-place form needs a power-of-two worker count")
     sc = build_scenario(mk(W, sizes, P, loss))
-    stats, got, ref = run_both(sc, ppm, acc_copies=2, acc_policy=policy)
+    stats, got, ref = run_both(sc, ppm, acc_copies=2, acc_policy=policy, result=result)
     assert stats["rel_to_addends"] <= FLOAT_TOL
     g1 = GpuRx(sc); g1.packetize_all()
     one = run_iteration(g1, sc, ppm)
@@ -135,12 +154,12 @@ def test_batches_alternate_between_accumulator_copies(queue):
     assert g.phase_signal()[0] == pytest.approx(o.phase_signal()[0], rel=1e-6)
 
 
-@pytest.mark.parametrize("place", [0, 2])
+@pytest.mark.parametrize("place", [0, 1])
 def test_automatic_copy_choice_on_a_buffer_large_enough_to_be_measured(place):
     """1.3 GB of packets: under the automatic policy the library times its probe kernel on the
-    buffer before the first batch (place 0: against two plain copies; place 2: against the one
-    copy it has, possibly adopting a second one it allocates then).  Whatever it decides, the
-    bits are those of a one-copy run."""
+    buffer before the first batch (place 0: against two plain copies; place 1: against the copy
+    the bounded search found, if it found one).  Whatever it decides, the bits are those of a
+    one-copy run."""
     sc = build_scenario(mk(8, [20_000_000, 15_000_000, 5_000_007], 366, 0.03, place="shuffle", order="shuffle"))
     g1 = GpuRx(sc, queue=True); g1.packetize_all()
     one = run_iteration(g1, sc, 20_000)
@@ -175,8 +194,94 @@ def test_accumulator_api():
     with pytest.raises(DblpError) as e:
         g.agg.accumulator_policy(4)
     assert e.value.code == binding.EINVAL
+    with pytest.raises(DblpError) as e:
+        g.agg.accumulator_copies(2, place=2)              # only 0 (plain) and 1 (bounded search) exist
+    assert e.value.code == binding.EINVAL
     g.agg.accumulator_copies(1)
     assert g.agg.accumulator_info()["copies"] == 1
+    with pytest.raises(DblpError) as e:
+        g.agg.accumulator_ptr(1)
+    assert e.value.code == binding.EINVAL
+    assert g.agg.accumulator_ptr(0) != 0
+
+
+def test_accumulator_modes_of_the_configuration():
+    """dblp_config.accumulator_mode: single (nothing measured), pair (plain second copy), search
+    (bounded: here a twentieth of the free memory and one second, so it may well find nothing and
+    must then run with one copy); caller-owned buffers; the combinations that are refused."""
+    import torch
+    import paper_2605_01989_amd as dblp
+    from paper_2605_01989_amd import DblpError, binding
+    sc = build_scenario(mk(4, [366 * 50 + 3, 900], 366, 0.1))
+    L = sc.L
+    mk_agg = lambda **kw: dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, **kw)
+    a = mk_agg()
+    assert a.accumulator_info()["copies"] == 1 and a.accumulator_info()["placement_steps"] == 0
+    b = mk_agg(accumulator_mode=binding.ACCMODE_PAIR)
+    assert b.accumulator_info()["copies"] == 2 and b.accumulator_ptr(1) != b.accumulator_ptr(0)
+    free0 = torch.cuda.mem_get_info()[0]
+    c = mk_agg(accumulator_mode=binding.ACCMODE_SEARCH, search_free_fraction=0.05, search_seconds=1.0)
+    info = c.accumulator_info()
+    assert info["copies"] in (1, 2) and info["placement_seconds"] < 3.0
+    assert torch.cuda.mem_get_info()[0] > free0 - (1 << 30)      # the search released what it held
+    buf = [torch.empty(L.N, dtype=torch.float32, device="cuda") for _ in range(2)]
+    d = mk_agg(d_accumulator=(buf[0], None))
+    assert d.accumulator_ptr(0) == buf[0].data_ptr()
+    with pytest.raises(DblpError) as e:
+        d.accumulator_copies(2)                           # the accumulator is the caller's
+    assert e.value.code == binding.EINVAL
+    e2 = mk_agg(accumulator_mode=binding.ACCMODE_PAIR, d_accumulator=(buf[0], buf[1]))
+    assert e2.accumulator_info()["copies"] == 2 and e2.accumulator_ptr(1) == buf[1].data_ptr()
+    for bad in (dict(accumulator_mode=3), dict(accumulator_mode=binding.ACCMODE_SEARCH, d_accumulator=(buf[0], None)),
+                dict(d_accumulator=(buf[0], buf[1])), dict(accumulator_mode=binding.ACCMODE_PAIR, d_accumulator=(buf[0], buf[0])),
+                dict(accumulator_mode=binding.ACCMODE_PAIR, d_accumulator=(buf[0], None)),
+                dict(d_accumulator=(buf[0][1:], None)), dict(search_free_fraction=0.95), dict(search_seconds=-1.0)):
+        with pytest.raises(DblpError) as e:
+            mk_agg(**bad)
+        assert e.value.code == binding.EINVAL, bad
+    # every mode gives the bits of the single-copy run
+    g1 = GpuRx(sc); g1.packetize_all()
+    one = run_iteration(g1, sc, 20_000)
+    for agg in (b, c, d, e2):
+        g = GpuRx(sc)
+        g.agg = agg
+        if agg in (d, e2):
+            g.d_out, g.result = buf[0], "caller"
+        g.packetize_all()
+        got = run_iteration(g, sc, 20_000)
+        assert np.array_equal(one["out"].view(np.uint32), got["out"].view(np.uint32)) and one["norm"] == got["norm"]
+
+
+def test_in_place_finalize_needs_a_power_of_two_worker_count_and_survives_later_arrivals():
+    from paper_2605_01989_amd import DblpError, binding
+    sc = build_scenario(mk(3, [500], 10))
+    g = GpuRx(sc, result="in_place"); g.packetize_all()
+    g.begin_round(sc.rnd_id)
+    g.apply(0, 150, None, None)
+    with pytest.raises(DblpError) as e:
+        g.finalize()
+    assert e.value.code == binding.EINVAL
+    # W = 4, two copies, alternating: finalize in place in the middle of the round (spans move to
+    # copy 0, missing spans are zeroed), then the rest arrives and finalize runs again
+    sc = build_scenario(mk(4, [366 * 90 + 11, 2000], 366, 0.1, place="shuffle", order="shuffle"))
+    L = sc.L
+    n = L.W * L.n_pkts
+    part = np.random.default_rng(3).integers(0, 3, size=n)
+    o, g = both(sc, acc_copies=2, acc_policy=3, result="in_place")
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        for k in range(3):
+            rx.apply(0, n, sc.batches[0].mask, np.flatnonzero(part == k).astype(np.uint32))
+            out = rx.finalize()
+            sig = rx.phase_signal() if k == 2 else None
+        rx.last = (out, sig)
+    from harness import abs_scale
+    ref, got = o.last[0], g.last[0].astype(np.float64)
+    scale = abs_scale(sc, sc.survive0)
+    nz = scale > 0
+    assert (np.abs(got - ref)[nz] / scale[nz]).max() <= FLOAT_TOL and np.all(got[~nz] == 0)
+    assert g.last[1][0] == pytest.approx(o.last[1][0], rel=1e-6)
+    assert np.array_equal(g.bitmap(), o.bitmap()) and g.counters() == o.counters()
 
 
 @pytest.mark.parametrize("queue", [False, True])
@@ -420,12 +525,12 @@ def test_phase_signal_on_a_vector_and_truth_table():
 def test_cfg1_full():
     stats, got, ref = run_both(build_scenario(wl.workload("cfg1")), 50_000)
     assert ref["counters"]["accepted"] >= int(0.985 * 16384)
-    print("cfg1", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+    record_stat("cfg1_full", dict(rounds=ref["rounds"], first_list=ref["probes"][0]["count"], **stats))
 
 
 def test_cfg2_full():
     stats, got, ref = run_both(build_scenario(wl.workload("cfg2")), 50_000)
-    print("cfg2", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+    record_stat("cfg2_full", dict(rounds=ref["rounds"], first_list=ref["probes"][0]["count"], **stats))
 
 
 def test_cfg3_schedule_scaled_down():
@@ -461,7 +566,7 @@ def test_cfg4_microburst_scaled_down():
     w = wl.scaled_down(wl.workload("cfg4"), 20_000_000)
     stats, got, ref = run_both(build_scenario(w), 80_000)
     assert ref["rounds"] >= 1
-    print("cfg4s", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+    record_stat("cfg4_scaled_down", dict(rounds=ref["rounds"], first_list=ref["probes"][0]["count"], **stats))
 
 
 def test_cfg5_chunked_scaled_down():
@@ -474,7 +579,50 @@ def test_cfg5_chunked_scaled_down():
     assert len(sc.batches) == 4
     stats, got, ref = run_both(sc, 20_000)
     assert ref["rounds"] >= 1
-    print("cfg5s", stats, "rounds", ref["rounds"], "list", ref["probes"][0]["count"])
+    record_stat("cfg5_chunked_scaled_down", dict(rounds=ref["rounds"], first_list=ref["probes"][0]["count"], **stats))
+
+
+def test_cfg5_schedule_scaled_down():
+    """The 1.3B-element recipe (W=32, 44-bucket chunk steps, Gilbert-Elliott loss at 5x rate, 1 %
+    heavy-tail entries) on 4M elements: 12 iterations of the continuous 2-15 % policy driven by the
+    phase signal (Eq. 1; Alg. Server, tolerance block), over the stretch of its gradient-scale
+    schedule that holds the x0.45 drop, plus one x0.75 step so that a bound in the middle of the
+    range occurs.  The bound fed to both sides comes from the oracle's signal; the GPU's signal
+    must map to the same 1000-ppm step every iteration."""
+    import oracle as orc
+    import paper_2605_01989_amd as dblp
+    w = wl.workload("cfg5")
+    L = w.layout
+    off, cnt = wl.buckets_fixed(4_000_000, L.P, 64)
+    sched = list(w.scale_schedule[6:16])
+    sched += [sched[-1] * 0.75, sched[-1] * 0.75 * 0.97]
+    w = dataclasses.replace(w, layout=wl.Layout(L.W, 4_000_000, L.P, off, cnt), scale_schedule=tuple(sched),
+                            iterations=len(sched))
+    pol = w.policy
+    assert pol["kind"] == "linear" and (pol["lo_ppm"], pol["hi_ppm"]) == (20_000, 150_000)
+    bound = pol["lo_ppm"]                         # first iteration: critical, tightest bound
+    prev_o = prev_g = None
+    seen, rounds = [], []
+    for it in range(w.iterations):
+        sc = build_scenario(w, it)
+        assert len(sc.batches) == 4
+        o, g = both(sc, queue=bool(it & 1))       # both hand-over forms take part
+        o.o.set_prev_norm(prev_o)
+        g.agg.set_prev_norm(prev_g)
+        ref = run_iteration(o, sc, bound)
+        got = run_iteration(g, sc, bound)
+        stats = compare_results(got, ref, sc)
+        prev_o, prev_g = ref["norm"], got["norm"]
+        nb_o = orc.policy_linear(ref["rel_delta"], pol["eta"], pol["lo_ppm"], pol["hi_ppm"])
+        nb_g = dblp.policy_linear(got["rel_delta"], pol["eta"], pol["lo_ppm"], pol["hi_ppm"])
+        assert nb_o == nb_g, (it, ref["rel_delta"], got["rel_delta"])
+        seen.append(bound); rounds.append(ref["rounds"])
+        bound = nb_o
+    record_stat("cfg5_schedule_scaled_down", dict(bounds=seen, rounds=rounds, **stats))
+    assert len(set(seen)) >= 3 and 20_000 in seen and max(seen) >= 140_000, seen
+    assert any(20_000 < b < 140_000 for b in seen), seen
+    assert seen.count(20_000) >= 3                # start, the iteration after it, the one after the x0.45 drop
+    assert max(rounds) >= 1
 
 
 def test_paper_burst_workload_with_epoch_controller():

@@ -216,6 +216,61 @@ def test_invalid_packets_are_rejected():
     assert np.allclose(rx.finalize(), definition_mean(sc, m), rtol=1e-15)
 
 
+@pytest.mark.parametrize("threads", [1, 3, 8])
+def test_thread_parallel_walk_equals_the_plain_walk_bit_for_bit(threads):
+    """The all-cores baseline splits the reconstruction buffer into disjoint element ranges, one per
+    thread; nothing observable may differ from the single-threaded arrival-order walk: bitmap,
+    the four counters, the fp64 sums (bitwise), lists and counts, with duplicates whose payloads
+    conflict, stale, invalid and lost packets in the stream."""
+    sc = build_scenario(tiny(5, [366 * 37 + 9, 1, 700, 366 * 4, 50], 366, loss=0.1, seed=17, place="shuffle", order="shuffle"))
+    L = sc.L
+    n = L.W * L.n_pkts
+    a, b = fresh(sc), fresh(sc)
+    for rx in (a, b):
+        p = rx.packets.reshape(-1, L.stride)
+        p[5, 4:6] = np.frombuffer(np.uint16(sc.rnd_id + 1).tobytes(), np.uint8)     # stale
+        p[6, 4:6] = np.frombuffer(np.uint16(sc.rnd_id + 1).tobytes(), np.uint8)     # stale and ...
+        p[6, 0:4] = np.frombuffer(np.uint32(L.n_pkts + 9).tobytes(), np.uint8)      # ... seq out of range
+        p[9, 6:8] = np.frombuffer(np.uint16(3).tobytes(), np.uint8)                  # wrong length
+        p[11, 0:4] = np.frombuffer(np.uint32(L.n_pkts).tobytes(), np.uint8)          # seq out of range
+        rx.src[20] = L.W                                                             # worker out of range
+        p[30, 0:8] = p[31, 0:8]                      # slot 30 now claims to be slot 31's packet,
+        rx.src[30] = rx.src[31]                      # from the same worker: a copy with a conflicting payload
+    bt = sc.batches[0]
+    order = np.concatenate([bt.order, bt.order[:60], [n + 3]]).astype(np.uint32)
+    a.apply(0, n, bt.mask, order)
+    used = b.o.apply_arrivals(b.packets, b.src, n, bt.mask, order, threads=threads)
+    assert used == threads
+    for rnd in range(1, 3):
+        ma, la, ca, meta = a.loss_account(30_000)
+        mb, lb, cb, metb = b.loss_account(30_000)
+        assert np.array_equal(ma, mb) and np.array_equal(la, lb) and (ca, meta) == (cb, metb)
+        slots = sc.resend(la, rnd)
+        a.apply(0, n, None, slots)
+        b.o.apply_arrivals(b.packets, b.src, n, None, slots, threads=threads)
+    assert a.counters() == b.counters() and a.counters()["duplicate"] >= 50 and a.counters()["invalid"] >= 4
+    assert np.array_equal(a.bitmap(), b.bitmap())
+    assert np.array_equal(a.o.acc().view(np.uint64), b.o.acc().view(np.uint64))
+
+
+def test_header_writer_gives_the_first_eight_bytes_of_every_packet():
+    """The header-only sender must write exactly what the packetiser puts in front of the payload,
+    at the same slots (ragged buckets, shuffled placement)."""
+    sc = build_scenario(tiny(3, [366 * 41 + 9, 1, 700, 366 * 3], 366, seed=13, place="shuffle"))
+    L = sc.L
+    n = L.W * L.n_pkts
+    rx = OracleRx(sc)
+    rx.packetize_all(rnd_id=0xA1B2)
+    headers = np.full(n * 8, 0xEE, dtype=np.uint8)
+    src = np.full(n, 0xFFFF, dtype=np.uint16)
+    for w in range(L.W):
+        rx.o.write_headers(w, 0xA1B2, 0, L.n_pkts, headers, src, slot_map=sc.slot_of[w])
+    assert np.array_equal(headers.reshape(n, 8), rx.packets.reshape(n, L.stride)[:, :8])
+    assert np.array_equal(src, rx.src)
+    lens = headers.reshape(n, 8)[:, 6].astype(int) | headers.reshape(n, 8)[:, 7].astype(int) << 8
+    assert sorted(set(lens.tolist())) == [1, 9, 334, 366]        # 700 = 366 + 334: short tails carry their own length
+
+
 def test_header_only_mode_gives_the_integer_outputs_of_the_full_receiver():
     """Alg. DBLP_RECV decides acceptance from the header alone (round, sequence number, length):
     a receiver that is shown only the 8 header bytes of every slot must end with the bitmap,
