@@ -115,6 +115,7 @@ def integer_outputs_in_full(job, probes, bound_ppm, counters, words):
         o.write_headers(wk, job.rnd_id, 0, L.n_pkts, headers, src, slot_map=job.slot_of[wk])
     o.begin_round(job.rnd_id)
     s0 = survive(job, 0)
+    print(f"{w.name}: header-only oracle: {n_slots} headers written", flush=True)
     for ci, ch in enumerate(job.chunks):
         local = (job.slot_of[:, ch["s0"]:ch["s1"]] - np.uint32(ch["base"])).astype(np.uint32)
         mask = wl.slot_mask_words(s0[:, ch["s0"]:ch["s1"]], local)
@@ -122,6 +123,7 @@ def integer_outputs_in_full(job, probes, bound_ppm, counters, words):
         o.apply_arrivals(headers[ch["base"] * 8:], src[ch["base"]:], ch["n"], mask, order, ch["n"],
                          accumulate=False, stride=8)
     for rnd, pr in enumerate(probes):
+        print(f"{w.name}: header-only oracle: probe {rnd}", flush=True)
         missing, lst, count, met = o.loss_account(bound_ppm)
         assert count == pr["count"] and met == pr["met"], f"probe {rnd}: list length / all-met differ"
         assert np.array_equal(missing, pr["missing"]), f"probe {rnd}: per-bucket counts differ"
@@ -185,7 +187,9 @@ def test_full_size_sampled_buckets_and_global_properties(name, BOUND_PPM, extra)
     sample = sorted({0, 1, *extra, L.B - 2, L.B - 1, *rng.choice(pool, size=min(64, pool.size), replace=False).tolist()})
     assert len(sample) >= 66
     agg_stats = dict(rel=0.0, plain_max=0.0, plain_above=0, n=0)
-    for b in sample:
+    for i, b in enumerate(sample):
+        if i % 8 == 0:
+            print(f"{name}: sampled bucket {i} of {len(sample)}", flush=True)
         rec, st = bucket_subproblem(job, b, probes, BOUND_PPM)
         s0, s1 = int(L.first_seq[b]), int(L.first_seq[b + 1])
         assert np.array_equal(rec_all[:, s0:s1], rec), f"bucket {b}: bitmap differs"
