@@ -69,6 +69,7 @@ class DeviceJob:
         self.place, self.order = place or w.place, order or w.order
         self.queue = queue   # first transmissions handed over as receive queues (else mask + order + worker table)
         self.both_forms_its = set(both_forms_its)
+        self.picks = None    # a list here collects the accumulator copy each receive-queue batch wrote new spans to
         self.rnd_id = 1
         mode = dict(one=binding.ACCMODE_SINGLE, pair=binding.ACCMODE_PAIR, search=binding.ACCMODE_SEARCH)[accumulator]
         self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5),
@@ -184,6 +185,8 @@ class DeviceJob:
         if self.queue:
             for ch, q in zip(self.chunks, m["queues"]):
                 agg.apply_arrivals_queue(self.packets[ch["base"] * st:], ch["n"], q)
+                if self.picks is not None:
+                    self.picks.append(agg.accumulator_info()["last_pick"])
         else:
             for ch, words in zip(self.chunks, m["words"]):
                 agg.apply_arrivals(self.packets[ch["base"] * st:], self.src[ch["base"]:], ch["n"], words,
@@ -404,7 +407,9 @@ def main():
         torch.cuda.synchronize()
         del a, b
     job.next_bound = first_bound(w)
+    job.picks = []
     warm = run_leg(job, w, list(range(args.warmup)))
+    picks, job.picks = job.picks[:len(job.chunks)], None
     for st in warm["per_step"]:
         log(f"[bench] warmup {st['it']}: bound={st['bound_ppm']} rounds={st['rounds']}")
     main_leg = run_leg(job, w, list(range(args.warmup, total)), profile=True)
@@ -433,6 +438,7 @@ def main():
     acc_info = agg.accumulator_info()
     acc_info.pop("last_pick")
     acc_info["mode"] = args.accumulator
+    acc_info["copy_per_chunk_step"] = "".join(str(p) for p in picks)
 
     def leg_summary(leg):
         acc = leg["accepted"]

@@ -450,6 +450,35 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
     return a;
 }
 
+// Epilogue of one 16-byte unit of a summed packet: scale, fold in the old accumulator value when the
+// span was written before (rmw is uniform over the wave), and keep the running sum of squares of
+// what is stored.  Written without per-element branches: positions outside the payload (the two
+// header words of unit 0, the tail beyond len) are carried along and masked out of the sum of
+// squares only; the writer never reads them.  o points at the accumulator element that packet
+// float position 4u corresponds to (only dereferenced where the position is payload).
+__device__ __forceinline__ float4 finish_unit(float4 a, float inv_w, bool rmw, const float* o, u32 u, u32 len, double& sq) {
+    float qv[4] = {a.x * inv_w, a.y * inv_w, a.z * inv_w, a.w * inv_w};
+    bool ok[4];
+    #pragma unroll
+    for (int c = 0; c < 4; ++c) { const u32 i4 = 4 * u + c; ok[c] = i4 >= 2 && i4 - 2 < len; }
+    if (rmw) {                                    // result = old value + this batch's sum
+        float ov[4];
+        #pragma unroll
+        for (int c = 0; c < 4; ++c) ov[c] = ok[c] ? o[c] : 0.f;      // four loads in flight, one wait
+        #pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            sq -= (double)ov[c] * (double)ov[c];
+            qv[c] = ov[c] + qv[c];
+        }
+    }
+    #pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const double d = (double)(ok[c] ? qv[c] : 0.f);
+        sq += d * d;
+    }
+    return make_float4(qv[0], qv[1], qv[2], qv[3]);
+}
+
 // One block per group of SUB consecutive sequence numbers, grid-stride over the groups the
 // batch touched.
 //   phase A  64 lanes = 4 workers x 16 packets per load of the arrival index: ballot -> new
@@ -461,7 +490,7 @@ __device__ __forceinline__ float4 sum_unit(const uint8_t* __restrict__ packets, 
 // The accumulator may exist in two copies (acc0, acc1; acc1 == acc0 when there is one): a span
 // written for the first time in this round goes to copy `pick` and home[seq] records it; a span
 // that earlier batches wrote is read and rewritten where home[seq] says it lives.
-__global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
+__global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu(8))) void gather_accumulate(Geo g, const uint8_t* __restrict__ packets,
                                                                     u64* __restrict__ pending, u64* __restrict__ bitmap,
                                                                     float* acc0, float* acc1,
                                                                     uint8_t* __restrict__ home, u32 pick,
@@ -542,17 +571,13 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) void gather_accumulate(Geo g, cons
                 const bool active = u < units;
                 const float4 a = sum_unit(packets, g.stride, u, active, sub, slot32);
                 if (active) {
-                    const float q[4] = {a.x, a.y, a.z, a.w};
+                    float* d = dst0 + 4 * u;                 // packet float position 4u+c -> d[c]
+                    const float4 r = finish_unit(a, inv_w, rmw, d, u, len, sq);
+                    const float q[4] = {r.x, r.y, r.z, r.w};
                     #pragma unroll
                     for (int c = 0; c < 4; ++c) {
                         const u32 i4 = 4 * u + c;
-                        if (i4 >= 2 && i4 - 2 < len) {
-                            float* d = dst0 + i4;
-                            float nv = q[c] * inv_w;
-                            if (rmw) { const float o = *d; sq -= (double)o * (double)o; nv = o + nv; }
-                            *d = nv;
-                            sq += (double)nv * (double)nv;
-                        }
+                        if (i4 >= 2 && i4 - 2 < len) d[c] = q[c];
                     }
                 }
             }
@@ -624,7 +649,7 @@ __device__ __forceinline__ void sum_packet(const uint8_t* __restrict__ packets, 
 
 // NP = 16-byte-unit passes per packet handled in one go (1..5), 0 = generic one pass at a time.
 template <int NP>
-__global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_staged(
+__global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_waves_per_eu(NP == 0 ? 7 : NP <= 3 ? 6 : NP == 4 ? 5 : 4))) void gather_accumulate_staged(
     Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
     float* acc0, float* acc1, uint8_t* __restrict__ home, u32 pick,
     const u64* __restrict__ counters, u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows, float inv_w,
@@ -761,21 +786,8 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                     for (int q = 0; q < (NP > 0 ? NP : 1); ++q) {
                         const u32 u = q * WAVE + lane;
                         if (u >= units) continue;
-                        float qv[4] = {a[q].x * inv_w, a[q].y * inv_w, a[q].z * inv_w, a[q].w * inv_w};
                         const float* o = acc + sh_elem[cur][t] - 2 + 4 * u;       // packet float position 4u+c -> o[c]
-                        #pragma unroll
-                        for (int c = 0; c < 4; ++c) {
-                            const u32 i4 = 4 * u + c;
-                            if (i4 >= 2 && i4 - 2 < len) {
-                                if (rmw) {                        // result = old value + this batch's sum
-                                    const float ov = o[c];
-                                    sq -= (double)ov * (double)ov;
-                                    qv[c] = ov + qv[c];
-                                }
-                                sq += (double)qv[c] * (double)qv[c];
-                            }
-                        }
-                        dstbuf[t * upp + u] = make_float4(qv[0], qv[1], qv[2], qv[3]);
+                        dstbuf[t * upp + u] = finish_unit(a[q], inv_w, rmw, o, u, len, sq);
                     }
                 }
             } else {
@@ -798,20 +810,7 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) void gather_accumulate_sta
                 if (lane == 0) sh_home[cur][t] = h;
                 if (active) {
                     const float* o = (h ? acc1 : acc0) + sh_elem[cur][t] - 2 + 4 * u;   // packet float position 4u+c -> o[c]
-                    float q[4] = {a.x * inv_w, a.y * inv_w, a.z * inv_w, a.w * inv_w};
-                    #pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        const u32 i4 = 4 * u + c;
-                        if (i4 >= 2 && i4 - 2 < len) {
-                            if (rmw) {      // earlier batches already wrote this span: result = old value + this batch's sum
-                                const float ov = o[c];
-                                sq -= (double)ov * (double)ov;
-                                q[c] = ov + q[c];
-                            }
-                            sq += (double)q[c] * (double)q[c];
-                        }
-                    }
-                    dstbuf[t * upp + u] = make_float4(q[0], q[1], q[2], q[3]);
+                    dstbuf[t * upp + u] = finish_unit(a, inv_w, rmw, o, u, len, sq);
                 }
             }
             }
