@@ -259,6 +259,20 @@ int dblp_finalize(dblp_ctx* ctx, int compensation, float* d_out);
 int dblp_phase_signal(dblp_ctx* ctx, const float* d_vec, double* h_norm, double* h_rel_delta,
                       int* h_critical);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the reduction of dblp_phase_signal(d_vec) without a context and without
+ * any allocation, here or in a library it calls.  *d_sumsq (DEVICE, 8-byte aligned) receives
+ * sum(d_vec[i]^2) in double over n_elems floats (DEVICE, 16-byte aligned), enqueued on `stream`
+ * of `device`; the caller takes the square root and applies Eq. 1 once the stream has reached
+ * that point.  The per-block partial sums live in a static device array of 32 KB that every GPU
+ * the library runs on holds until the process ends; all calls on one GPU share it, so calls that
+ * overlap on one GPU (different streams, different threads) race: order them.  The array keeps
+ * the last call's contents; every call overwrites what it reads.  Limits: n_elems 1..2^36,
+ * device 0..15; beyond them EINVAL.  Same arithmetic and block order as dblp_phase_signal, hence
+ * the same bits.  dblp_sumsq_static_error() gives the text of this thread's last failure. */
+int dblp_sumsq_static(int device, void* stream, const float* d_vec, uint64_t n_elems, double* d_sumsq);
+const char* dblp_sumsq_static_error(void);
+
 /* Copies the bitmap, W x bitmap_words_per_worker words, bit seq%64 of word seq/64. */
 int dblp_get_bitmap(dblp_ctx* ctx, uint64_t* d_bitmap_out);
 

@@ -6,4 +6,4 @@ in the library's kernels.  There is no CPU fallback; a missing library is an
 error.
 """
 from .binding import (Aggregator, ClrController, DblpError, lib, policy_linear, policy_three_level,  # noqa: F401
-                      policy_two_level)
+                      policy_two_level, sumsq_static)

@@ -24,7 +24,8 @@ ACCMODE_SINGLE, ACCMODE_PAIR, ACCMODE_SEARCH = 0, 1, 2
 EXPORTS = ["dblp_create", "dblp_destroy", "dblp_layout", "dblp_accumulator_copies", "dblp_accumulator_policy", "dblp_accumulator_info", "dblp_accumulator_ptr", "dblp_begin_round", "dblp_packetize", "dblp_packetize_list",
            "dblp_apply_arrivals", "dblp_apply_arrivals_queue", "dblp_loss_account", "dblp_finalize", "dblp_phase_signal",
            "dblp_get_bitmap", "dblp_get_counters", "dblp_set_prev_norm", "dblp_get_prev_norm",
-           "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear", "dblp_clr_init", "dblp_clr_step"]
+           "dblp_last_error", "dblp_profile_enable", "dblp_profile_read", "dblp_policy_two_level", "dblp_policy_three_level", "dblp_policy_linear", "dblp_clr_init", "dblp_clr_step",
+           "dblp_sumsq_static", "dblp_sumsq_static_error"]
 
 
 class DblpError(RuntimeError):
@@ -93,6 +94,8 @@ def lib():
         L.dblp_clr_init.argtypes = [ctypes.POINTER(ClrState), u32, u32, u32]
         L.dblp_clr_step.argtypes = [ctypes.POINTER(ClrState), i32]
         L.dblp_clr_step.restype = u32
+        L.dblp_sumsq_static.argtypes = [i32, vp, vp, u64, vp]
+        L.dblp_sumsq_static_error.restype = ctypes.c_char_p
         L.dblp_policy_two_level.argtypes = [i32, u32, u32]
         L.dblp_policy_three_level.argtypes = [dbl, dbl, u32, u32, u32]
         L.dblp_policy_linear.argtypes = [dbl, dbl, u32, u32]
@@ -110,6 +113,16 @@ def policy_three_level(rel_delta: float, eta: float, tight_ppm: int, mid_ppm: in
 
 def policy_linear(rel_delta: float, eta: float, lo_ppm: int, hi_ppm: int) -> int:
     return int(lib().dblp_policy_linear(rel_delta, eta, lo_ppm, hi_ppm))
+
+
+def sumsq_static(d_vec, d_sumsq, n_elems=None, device=0, stream=None):
+    """dblp_sumsq_static: sum of squares of a device vector into a device double, allocating nothing."""
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream(device).cuda_stream
+    rc = lib().dblp_sumsq_static(device, stream, _ptr(d_vec), d_vec.numel() if n_elems is None else n_elems, _ptr(d_sumsq))
+    if rc != OK:
+        raise DblpError(rc, lib().dblp_sumsq_static_error().decode())
 
 
 class ClrController:

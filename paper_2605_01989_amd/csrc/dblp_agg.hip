@@ -1826,6 +1826,49 @@ extern "C" int dblp_phase_signal(dblp_ctx* c, const float* d_vec, double* h_norm
     return DBLP_OK;
 }
 
+// ------------------------------------------------------------------------------------------
+// sum of squares without any allocation: per-block partial sums in a static device array
+// ------------------------------------------------------------------------------------------
+#define STATIC_PARTIALS 4096                    // blocks of one launch at most; 32 KB per GPU
+#define STATIC_MAX_ELEMS (1ull << 36)           // 64 Gi floats: more than any one GPU holds
+#define STATIC_MAX_DEVICES 16
+static __device__ __align__(256) double static_partials[STATIC_PARTIALS];
+static double* static_partials_ptr[STATIC_MAX_DEVICES];     // device address of the array on each GPU
+static int static_cus[STATIC_MAX_DEVICES];
+static thread_local char static_err[160] = "";
+
+extern "C" const char* dblp_sumsq_static_error(void) { return static_err; }
+
+extern "C" int dblp_sumsq_static(int device, void* stream, const float* d_vec, uint64_t n_elems, double* d_sumsq) {
+    if (device < 0 || device >= STATIC_MAX_DEVICES) { snprintf(static_err, sizeof static_err, "sumsq_static: device ordinal outside 0..%d", STATIC_MAX_DEVICES - 1); return DBLP_EINVAL; }
+    if (!d_vec || !d_sumsq) { snprintf(static_err, sizeof static_err, "sumsq_static: null pointer"); return DBLP_EINVAL; }
+    if (((uintptr_t)d_vec & 15) != 0 || ((uintptr_t)d_sumsq & 7) != 0) { snprintf(static_err, sizeof static_err, "sumsq_static: d_vec must be 16-byte and d_sumsq 8-byte aligned"); return DBLP_EINVAL; }
+    if (n_elems == 0 || n_elems > STATIC_MAX_ELEMS) { snprintf(static_err, sizeof static_err, "sumsq_static: n_elems must be 1..2^36"); return DBLP_EINVAL; }
+    hipError_t e = hipSetDevice(device);
+    if (e != hipSuccess) { snprintf(static_err, sizeof static_err, "sumsq_static: hipSetDevice: %s", hipGetErrorString(e)); return DBLP_EHIP; }
+    if (!static_partials_ptr[device]) {         // once per device: where this GPU keeps its copy of the array
+        double* p = nullptr;
+        e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(static_partials));
+        if (e != hipSuccess || !p) { snprintf(static_err, sizeof static_err, "sumsq_static: hipGetSymbolAddress: %s", hipGetErrorString(e)); (void)hipGetLastError(); return DBLP_EHIP; }
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+        if (e != hipSuccess || cus <= 0) { (void)hipGetLastError(); cus = 256; }
+        static_cus[device] = cus;
+        static_partials_ptr[device] = p;
+    }
+    double* partials = static_partials_ptr[device];
+    u64 blocks = (n_elems / 4 + 255) / 256;     // the grid rule of dblp_phase_signal, so the two agree to the bit
+    const u64 cap = (u64)static_cus[device] * FIN_BLOCKS_PER_CU < STATIC_PARTIALS ? (u64)static_cus[device] * FIN_BLOCKS_PER_CU : STATIC_PARTIALS;
+    if (blocks > cap) blocks = cap;
+    if (blocks == 0) blocks = 1;
+    hipLaunchKernelGGL(sumsq_vec, dim3((u32)blocks), dim3(256), 0, (hipStream_t)stream, d_vec, (u64)n_elems, partials);
+    hipLaunchKernelGGL(reduce_partials, dim3(1), dim3(256), 0, (hipStream_t)stream, (const double*)partials, (u32)blocks, d_sumsq);
+    e = hipGetLastError();
+    if (e != hipSuccess) { snprintf(static_err, sizeof static_err, "sumsq_static: launch: %s", hipGetErrorString(e)); return DBLP_EHIP; }
+    static_err[0] = 0;
+    return DBLP_OK;
+}
+
 extern "C" int dblp_get_bitmap(dblp_ctx* c, uint64_t* d_out) {
     if (!c || !d_out) return DBLP_EINVAL;
     HIP_TRY(c, hipSetDevice(c->device));
