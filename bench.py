@@ -166,6 +166,55 @@ class DeviceJob:
         worker = self.src[ch["base"]: ch["base"] + ch["n"]][slots].long() & 0xFFFF
         return slots | (worker << 32)
 
+    def sender_timing(self, reps: int = 5) -> dict:
+        """Sender side (Alg. "DBLP Send"), timed on its own and never part of `value`: the range
+        packetiser on the first chunk step of every worker (the resident packets are rewritten with
+        the bytes they already hold), and the list packetiser on the retransmit list that a probe
+        with bound 0 gives after that chunk step alone.  Algorithmic bytes per packet: 4*len read +
+        stride written."""
+        torch, wl, w, L, agg = self.torch, self.wl, self.w, self.L, self.agg
+        stream = torch.cuda.current_stream().cuda_stream
+        ch = self.chunks[0]
+        ne, npk = ch["e1"] - ch["e0"], ch["s1"] - ch["s0"]
+        grads = []
+        for wk in range(L.W):
+            g = torch.empty(ne, dtype=torch.float32, device="cuda")
+            wl.grad_fill_device(g.data_ptr(), w.seed, wk, 0, ch["e0"], ne, w.sigma_at(0), w.tail_ppm, w.tail_mul, stream)
+            grads.append(g)
+        maps = [self.d_slot_of[wk * L.n_pkts + ch["s0"]: wk * L.n_pkts + ch["s1"]] for wk in range(L.W)]
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        out = {}
+
+        def timed(fn, n_bytes, n_calls):
+            fn()
+            torch.cuda.synchronize()
+            ev[0].record()
+            for _ in range(reps):
+                fn()
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1]) / reps
+            return dict(GBps=round(n_bytes / ms / 1e6, 1), hbm_frac=round(n_bytes / ms / 1e6 / HBM_PEAK_GBPS, 4),
+                        ms=round(ms, 4), calls=n_calls, algorithmic_bytes=int(n_bytes))
+
+        def all_workers():
+            for wk in range(L.W):
+                agg.packetize(wk, self.rnd_id, grads[wk], ch["e0"], ch["s0"], npk, self.packets, self.src,
+                              d_slot_map=maps[wk], n_slots=self.n_slots)
+        out["packetize"] = timed(all_workers, L.W * (4 * ne + npk * L.stride), L.W)
+        if ch["e0"] == 0:
+            # a long retransmit list over this chunk step's sequence range: every fourth packet of every worker
+            seqs = torch.arange(ch["s0"], ch["s1"], 4, device="cuda", dtype=torch.int64)
+            lst = (torch.arange(L.W, device="cuda", dtype=torch.int64)[:, None] << 32 | seqs[None, :]).reshape(-1).contiguous()
+            n = int(lst.numel())
+            stage = torch.empty(n * L.stride, dtype=torch.uint8, device="cuda")
+            stage_src = torch.empty(n, dtype=torch.int16, device="cuda")
+            fill = L.N / (L.n_pkts * L.P)
+            out["packetize_list"] = timed(lambda: agg.packetize_list(self.rnd_id, grads, lst, n, stage, stage_src),
+                                          n * (4 * L.P * fill + L.stride), 1)
+            out["packetize_list"]["entries"] = n
+        return out
+
     def use_single_accumulator(self):
         """Switch the context to one accumulator copy (d_out is a view of it: refreshed here)."""
         self.d_out = None
@@ -406,6 +455,7 @@ def main():
         b.copy_(a)          # reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del a, b
+    sender = job.sender_timing()
     job.next_bound = first_bound(w)
     job.picks = []
     warm = run_leg(job, w, list(range(args.warmup)))
@@ -478,7 +528,7 @@ def main():
                retransmission_rounds=main_leg["rounds"], resent_packets=main_leg["resent"],
                gpu_event_ms_per_step=round(main_leg["event_ms"] / args.steps, 3),
                kernel_ms_per_step={k: round(v[0] / args.steps, 4) for k, v in prof.items()},
-               other_forms=other, per_step=main_leg["per_step"], roofline=roofline)
+               sender_side_not_in_value=sender, other_forms=other, per_step=main_leg["per_step"], roofline=roofline)
     if not args.no_cpu_baseline:
         del job
         torch.cuda.empty_cache()
