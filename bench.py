@@ -83,6 +83,8 @@ class DeviceJob:
         self.d_missing = torch.empty(L.W * L.B, dtype=torch.int32, device=dev)
         self.list_cap = max(self.n_slots // 8, 1 << 16)
         self.d_list = torch.empty(self.list_cap, dtype=torch.int64, device=dev)
+        self.d_resend = torch.empty(self.list_cap, dtype=torch.int32, device=dev)    # slots of the packets sent again
+        self.stream = torch.cuda.current_stream().cuda_stream
         # placement and arrival orders (host generated, seeded)
         self.slot_of = wl.placement_chunked(self.place, L, w.chunk_buckets, w.seed, 0)
         self.d_slot_of = torch.from_numpy(self.slot_of.reshape(-1).view(np.int32)).to(dev)
@@ -253,20 +255,20 @@ class DeviceJob:
                 break
             rounds += 1
             # the simulated sender + network: resend the listed packets, redraw their loss
-            lst = self.d_list[:count]
-            idx = (lst >> 32) * L.n_pkts + (lst & 0xFFFFFFFF)
+            self.wl.resend_slots_device(self.d_list.data_ptr(), count, self.d_slot_of.data_ptr(), L.n_pkts,
+                                        self.d_resend.data_ptr(), self.stream)
             if self.per_iteration_retx and rounds <= self.w.drawn_rounds:
                 d_s = torch.from_numpy(self.w.survive(it, rounds, self.slot_of).reshape(-1)).cuda()
-                idx = idx[d_s[idx].bool()]
-                slots = self.d_slot_of[idx]
+                lst = self.d_list[:count]
+                idx = (lst >> 32) * L.n_pkts + (lst & 0xFFFFFFFF)
+                slots = self.d_resend[:count][d_s[idx].bool()]
                 resent += int(slots.numel())
                 agg.apply_arrivals(self.packets, self.src, self.n_slots, None, slots, slots.numel())
             else:
                 # every listed packet is sent again; the ones this round's loss draw takes are masked
                 # out (lost on the wire: never looked at).  No host round trip besides the probe's.
-                slots = self.d_slot_of[idx]
                 words = self.d_survive_words.get(rounds)
-                agg.apply_arrivals(self.packets, self.src, self.n_slots, words, slots, count)
+                agg.apply_arrivals(self.packets, self.src, self.n_slots, words, self.d_resend, count)
                 if words is not None:
                     resent = None          # survivors not counted here: the caller derives them from the accepted counter
                 elif resent is not None:

@@ -413,13 +413,16 @@ __global__ __launch_bounds__(256) void index_arrivals(Geo g, const uint8_t* __re
     }
 }
 
-// Folds the per-block tallies of one index launch into the context's counters: round totals are
-// added to, the batch's candidate count and touched seq range are set.  One block.
-__global__ __launch_bounds__(256) void fold_index_tallies(const u32* __restrict__ block_tallies, u32 n_blocks,
-                                                          u64* __restrict__ counters) {
-    __shared__ u32 sh[4][5];
+// What the gather kernels need to know about the batch: the touched sequence range and the number
+// of candidates.  Every block of a gather launch adds up the index launch's per-block tallies
+// itself (n_rows rows of 5 words, read from L2), which saves a launch between the two passes; the
+// block that `owner` names also adds the totals to the round's counters (one block of one launch
+// per batch).  All threads of the block must call this; sh holds 5 words per wave.
+struct BatchInfo { u64 lo, hi, cand; };
+__device__ __forceinline__ BatchInfo fold_index_tallies(const u32* __restrict__ block_tallies, u32 n_rows, u64* __restrict__ counters,
+                                                        bool owner, u32* sh) {
     u32 t0 = 0, t1 = 0, t2 = 0, lo = 0xFFFFFFFFu, hi = 0;
-    for (u32 b = threadIdx.x; b < n_blocks; b += 256) {
+    for (u32 b = threadIdx.x; b < n_rows; b += blockDim.x) {
         const u32* row = block_tallies + (u64)b * 5;
         t0 += row[0]; t1 += row[1]; t2 += row[2];
         lo = row[3] < lo ? row[3] : lo;
@@ -427,24 +430,25 @@ __global__ __launch_bounds__(256) void fold_index_tallies(const u32* __restrict_
     }
     t0 = wave_reduce<OpAdd>(t0); t1 = wave_reduce<OpAdd>(t1); t2 = wave_reduce<OpAdd>(t2);
     lo = wave_reduce<OpMin>(lo); hi = wave_reduce<OpMax>(hi);
-    const u32 wave = threadIdx.x / WAVE;
-    if (lane_id() == 0) { sh[wave][0] = t0; sh[wave][1] = t1; sh[wave][2] = t2; sh[wave][3] = lo; sh[wave][4] = hi; }
+    const u32 wave = threadIdx.x / WAVE, n_waves = blockDim.x / WAVE;
+    if (lane_id() == 0) { sh[wave * 5 + 0] = t0; sh[wave * 5 + 1] = t1; sh[wave * 5 + 2] = t2; sh[wave * 5 + 3] = lo; sh[wave * 5 + 4] = hi; }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        u64 s0 = 0, s1 = 0, s2 = 0;
-        u32 l = 0xFFFFFFFFu, h = 0;
-        for (int i = 0; i < 4; ++i) {
-            s0 += sh[i][0]; s1 += sh[i][1]; s2 += sh[i][2];
-            l = sh[i][3] < l ? sh[i][3] : l;
-            h = sh[i][4] > h ? sh[i][4] : h;
-        }
+    u64 s0 = 0, s1 = 0, s2 = 0;
+    u32 l = 0xFFFFFFFFu, h = 0;
+    for (u32 i = 0; i < n_waves; ++i) {
+        s0 += sh[i * 5 + 0]; s1 += sh[i * 5 + 1]; s2 += sh[i * 5 + 2];
+        l = sh[i * 5 + 3] < l ? sh[i * 5 + 3] : l;
+        h = sh[i * 5 + 4] > h ? sh[i * 5 + 4] : h;
+    }
+    __syncthreads();                                // sh may be reused by the caller
+    if (owner && threadIdx.x == 0) {
         counters[C_STALE] += s0;
         counters[C_INVALID] += s1;
         counters[C_CANDIDATES] += s2;
-        counters[C_BATCH_CAND] = s2;
-        counters[C_LO] = s2 ? (u64)l : NONE64;
-        counters[C_HI] = s2 ? (u64)h : 0;
     }
+    BatchInfo bi;
+    bi.cand = s2; bi.lo = s2 ? (u64)l : NONE64; bi.hi = s2 ? (u64)h : 0;
+    return bi;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -467,9 +471,8 @@ __global__ __launch_bounds__(256) void fold_index_tallies(const u32* __restrict_
 // (independent waves, no staging pipeline to fill per group), dense ones the staged kernel; both
 // are launched and the one whose regime it is not returns at once.
 #define SPARSE_DIV 8
-__device__ __forceinline__ bool batch_is_sparse(const u64* counters, u32 W) {
-    const u64 lo = counters[C_LO], hi = counters[C_HI];
-    return counters[C_BATCH_CAND] * SPARSE_DIV < (hi - lo) * W;
+__device__ __forceinline__ bool batch_is_sparse(const BatchInfo& bi, u32 W) {
+    return bi.cand * SPARSE_DIV < (bi.hi - bi.lo) * W;
 }
 
 // Sum the payload unit `u` (16 bytes at offset 16u of each packet) over the workers in `sub`
@@ -540,7 +543,8 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
                                                                     u64* __restrict__ pending, u64* __restrict__ bitmap,
                                                                     float* acc0, float* acc1,
                                                                     uint8_t* __restrict__ home, u32 pick,
-                                                                    const u64* __restrict__ counters,
+                                                                    const u32* __restrict__ block_tallies, u32 n_tally_rows,
+                                                                    u64* __restrict__ counters, int tally_owner,
                                                                     u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows,
                                                                     float inv_w, int only_if_sparse) {
     extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB]
@@ -548,9 +552,11 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
     __shared__ u32 sh_len[SUB];
     __shared__ u32 sh_new[GA_WAVES], sh_old[GA_WAVES];
     __shared__ double sh_sq[GA_WAVES];
-    const u64 lo = counters[C_LO], hi = counters[C_HI];
+    __shared__ u32 sh_tally[GA_WAVES * 5];
+    const BatchInfo bi = fold_index_tallies(block_tallies, n_tally_rows, counters, tally_owner && blockIdx.x == 0, sh_tally);
+    const u64 lo = bi.lo, hi = bi.hi;
     if (hi == 0) return;                                    // no candidate in this batch
-    if (only_if_sparse && !batch_is_sparse(counters, g.W)) return;
+    if (only_if_sparse && !batch_is_sparse(bi, g.W)) return;
     const u32 lane = lane_id();
     const u32 wave = threadIdx.x / WAVE;
     const u32 W = g.W;
@@ -698,7 +704,8 @@ template <int NP>
 __global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_waves_per_eu(NP == 0 ? 7 : NP <= 3 ? 6 : NP == 4 ? 5 : 4))) void gather_accumulate_staged(
     Geo g, const uint8_t* __restrict__ packets, u64* __restrict__ pending, u64* __restrict__ bitmap,
     float* acc0, float* acc1, uint8_t* __restrict__ home, u32 pick,
-    const u64* __restrict__ counters, u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows, float inv_w,
+    const u32* __restrict__ block_tallies, u32 n_tally_rows, u64* __restrict__ counters, int whole_batch,
+    u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows, float inv_w,
     u32 sub, u32 sub_log2, u32 n_pass, u32 table_in_lds) {
     extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, slots, bucket table
     __shared__ double sh_sq[GS_READERS];
@@ -707,9 +714,12 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_wave
     __shared__ u32 sh_home[2][SUB];                 // accumulator copy each packet of the group goes to
     __shared__ u32 sh_flag_new[2];
     __shared__ u32 sh_new[GS_READERS], sh_old[GS_READERS];
-    const u64 lo = counters[C_LO], hi = counters[C_HI];
+    __shared__ u32 sh_tally[(GS_READERS + 1) * 5];
+    // this launch is the first of the batch's gather launches: its block 0 books the index pass's tallies
+    const BatchInfo bi = fold_index_tallies(block_tallies, n_tally_rows, counters, blockIdx.x == 0, sh_tally);
+    const u64 lo = bi.lo, hi = bi.hi;
     if (hi == 0) return;                            // no candidate in this batch (uniform over the grid)
-    if (batch_is_sparse(counters, g.W)) return;     // left to the direct kernel
+    if (!whole_batch && batch_is_sparse(bi, g.W)) return;     // left to the direct kernel
     const u32 lane = lane_id();
     const u32 wave = threadIdx.x / WAVE;
     const u32 n_readers = blockDim.x / WAVE - 1;      // the last wave of the block is the writer
@@ -999,19 +1009,32 @@ __global__ __launch_bounds__(256) void finalize_pass(Geo g, const u64* __restric
                                                      const float* acc1, uint8_t* __restrict__ home,
                                                      float* out, int scale_mode, float wf, int move_home,
                                                      double* __restrict__ partials, u32 n_work_blocks,
-                                                     const double* __restrict__ sumsq_rows, u32 n_rows,
-                                                     double* __restrict__ mailbox) {
+                                                     const double* __restrict__ sumsq_rows, const u64* __restrict__ accept_rows,
+                                                     u32 n_rows, u64* __restrict__ counters, u64* __restrict__ mailbox) {
     __shared__ double wsum[4];
+    __shared__ u64 asum[4];
     extern __shared__ u32 fs_lds[];             // bucket boundaries (B + 1 words) when TABLE_IN_LDS
     const u32 lane = lane_id();
     const u32 wave_in_block = threadIdx.x / WAVE;
-    if (blockIdx.x >= n_work_blocks) {          // the extra block: fixed-order sum of the gather's rows
+    if (blockIdx.x >= n_work_blocks) {
+        // the extra block: fixed-order sum of the gather's rows (sum of squares for Eq. 1, accepted
+        // packets), and the round's counters mirrored into the host mailbox:
+        // mailbox[1] = sum of squares (when the gather kept it), mailbox[8..11] = accepted,
+        // candidates, stale, invalid
         double s = 0.0;
-        for (u32 i = threadIdx.x; i < n_rows; i += 256) s += sumsq_rows[i];
+        u64 a = 0;
+        for (u32 i = threadIdx.x; i < n_rows; i += 256) { s += sumsq_rows[i]; a += accept_rows[i]; }
         s = wave_sum_f64(s);
-        if (lane == 0) wsum[wave_in_block] = s;
+        const u32 a_lo = wave_reduce<OpAdd>((u32)(a & 0xFFFFFu)), a_hi = wave_reduce<OpAdd>((u32)(a >> 20));   // 64 x 2^20 fits 32 bits
+        if (lane == 0) { wsum[wave_in_block] = s; asum[wave_in_block] = ((u64)a_hi << 20) + a_lo; }
         __syncthreads();
-        if (threadIdx.x == 0) mailbox[0] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+        if (threadIdx.x == 0) {
+            const u64 accepted = (asum[0] + asum[1]) + (asum[2] + asum[3]);
+            counters[C_ACCEPTED] = accepted;
+            if (scale_mode == 0) ((double*)mailbox)[1] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+            mailbox[8] = accepted; mailbox[9] = counters[C_CANDIDATES];
+            mailbox[10] = counters[C_STALE]; mailbox[11] = counters[C_INVALID];
+        }
         return;
     }
     const u32* fs = g.first_seq;
@@ -1209,6 +1232,8 @@ struct dblp_ctx {
     double search_seconds;  // its time limit
     int fold;               // W is a power of two: the gather stores sum / W
     int norm_in_mailbox;    // the last finalize left the sum of squares in the host mailbox
+    int counters_in_mailbox; // ... and the round's counters (until the next batch or round)
+    int mailbox_seen;       // the stream has been synchronised since that finalize
     int acc_policy;         // DBLP_ACC_*
     int last_pick;          // copy the last batch wrote new spans to
     u32 batch_no;
@@ -1220,7 +1245,7 @@ struct dblp_ctx {
     u32* d_block_tallies;   // [IDX_BLOCKS_PER_CU * n_cus][5], written by index_arrivals
     u64* d_accept_rows;     // [2][ACCEPT_ROWS] accepted packets per gather block (staged grid, direct grid)
     double* d_sumsq_rows;   // [2][ACCEPT_ROWS] sum of squares of what each gather block stored (same allocation)
-    u64* h_mailbox;         // pinned host memory, 8 x u64, also mapped into the device
+    u64* h_mailbox;         // pinned host memory, 16 x u64, also mapped into the device
     u64* d_mailbox;         // device address of h_mailbox
     // host copies of the geometry
     u32* h_first_seq; u64* h_b_off; u64* h_b_cnt;
@@ -1339,7 +1364,7 @@ static int set_accumulator_copies(dblp_ctx* c, int copies, int place) {
     if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, DBLP_EHIP, "accumulator_copies: synchronize");
     for (int i = 0; i < 2; ++i) { if (c->acc_alloc[i]) (void)hipFree(c->acc_alloc[i]); c->acc_alloc[i] = nullptr; }
     c->n_acc = 1; c->acc_distinct = 0; c->place_ms[0] = c->place_ms[1] = 0.f; c->place_steps = 0; c->place_seconds = 0.0;
-    c->n_picked = 0; c->last_pick = 0; c->round_open = 0; c->finalized = 0; c->norm_in_mailbox = 0;
+    c->n_picked = 0; c->last_pick = 0; c->round_open = 0; c->finalized = 0; c->norm_in_mailbox = 0; c->counters_in_mailbox = 0;
     const size_t bytes = (c->N * sizeof(float) + 255) / 256 * 256;     // the scratch area starts aligned
     const size_t scratch = copies == 2 ? CLS_SCRATCH_BYTES : 0;
     if (hipMalloc(&c->acc_alloc[0], bytes + scratch) != hipSuccess) { (void)hipGetLastError(); return fail(c, DBLP_ENOMEM, "accumulator"); }
@@ -1523,7 +1548,7 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     ok = ok && hipMalloc(&c->d_partials, max_partials * sizeof(double)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_accept_rows, 4 * ACCEPT_ROWS * sizeof(u64)) == hipSuccess;   // + the sum-of-squares rows
     ok = ok && hipMalloc(&c->d_block_tallies, (size_t)c->n_cus * IDX_BLOCKS_PER_CU * 5 * sizeof(u32)) == hipSuccess;
-    ok = ok && hipHostMalloc((void**)&c->h_mailbox, 8 * sizeof(u64), hipHostMallocMapped) == hipSuccess;
+    ok = ok && hipHostMalloc((void**)&c->h_mailbox, 16 * sizeof(u64), hipHostMallocMapped) == hipSuccess;
     if (!ok) { (void)hipGetLastError(); dblp_destroy(c); return DBLP_ENOMEM; }
     ok = ok && hipHostGetDevicePointer((void**)&c->d_mailbox, c->h_mailbox, 0) == hipSuccess;
     ok = ok && hipMemcpyAsync(c->d_first_seq, c->h_first_seq, (B + 1) * sizeof(u32), hipMemcpyHostToDevice, c->stream) == hipSuccess;
@@ -1610,7 +1635,7 @@ extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
     hipLaunchKernelGGL(reset_round, dim3(grid_for(c, (n + 4 * ACCEPT_ROWS + 255) / 256, 16)), dim3(256), 0, c->stream,
                        c->d_bitmap, n, c->d_accept_rows, (u64)(4 * ACCEPT_ROWS), c->d_counters);
     LAUNCH_CHECK(c, "begin_round");
-    c->round = round; c->round_open = 1; c->finalized = 0; c->norm_in_mailbox = 0;
+    c->round = round; c->round_open = 1; c->finalized = 0; c->norm_in_mailbox = 0; c->counters_in_mailbox = 0;
     return DBLP_OK;
 }
 
@@ -1711,6 +1736,7 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
     const int pick = pick_copy(c, d_packets, n_slots * g.stride, n_slots, n_arrivals);
     c->last_pick = pick;
     ++c->batch_no;
+    u32 n_tally_rows = 0;
     {
         ProfScope ps(c, DBLP_K_INDEX);
         const u32 grid = grid_for(c, (n_arrivals + 255) / 256, IDX_BLOCKS_PER_CU);
@@ -1721,14 +1747,26 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
         hipLaunchKernelGGL(idx, dim3(grid), dim3(256), table <= IDX_TABLE_LDS_MAX ? table : 0, c->stream, g,
                            (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
                            (const u64*)d_queue, (u64)n_arrivals, (u32)c->round, c->d_pending, c->d_block_tallies);
-        hipLaunchKernelGGL(fold_index_tallies, dim3(1), dim3(256), 0, c->stream, c->d_block_tallies, grid, c->d_counters);
+        n_tally_rows = grid;
     }
     const float inv_w = c->fold ? 1.0f / (float)g.W : 1.0f;   // exact for the powers of two it is used with
     {
         ProfScope ps(c, DBLP_K_GATHER);
         u32 sub = SUB, sub_log2 = 4;
         while (sub >= 2 && 2u * sub * g.stride > GS_LDS_BUDGET) { sub >>= 1; --sub_log2; }
-        if (sub >= 2) {   // two groups of packets fit in LDS: readers + writer wave
+        // Which gather kernel: the staged one for dense batches, the direct one for sparse ones
+        // (and for packets too long to stage).  Where the number of arrivals settles it, only that
+        // one is launched: at least one arrival per SPARSE_DIV (worker, seq) pairs of the whole
+        // round is dense whatever range it touches; fewer than one per 8 * SPARSE_DIV pairs is
+        // taken as sparse.  In between both are launched and each decides on the device, from the
+        // sequence range the index pass found, whether the batch is its own.
+        const u64 pairs = (u64)g.W * g.n_pkts;
+        const bool can_stage = sub >= 2;
+        const bool surely_dense = can_stage && n_arrivals * SPARSE_DIV >= pairs;
+        const bool surely_sparse = n_arrivals * SPARSE_DIV * 8 < pairs;
+        const bool launch_staged = can_stage && !surely_sparse;
+        const bool launch_direct = !surely_dense;
+        if (launch_staged) {   // two groups of packets fit in LDS: readers + writer wave
             const u32 wpl = WAVE / sub;
             size_t lds = 2ull * sub * g.stride + (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
             const size_t table = ((size_t)g.B + 1) * sizeof(u32);
@@ -1741,26 +1779,27 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
             if (per_cu > GS_MAX_PER_CU) per_cu = GS_MAX_PER_CU;
             if (per_cu < 1) per_cu = 1;
-            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u64*, u64*, double*, float, u32, u32, u32, u32) =
+            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u32*, u32, u64*, int, u64*, double*, float, u32, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
             hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, per_cu)), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
-                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows, c->d_sumsq_rows, inv_w,
-                               sub, sub_log2, n_pass, table_in_lds);
+                               c->d_acc[1], c->d_home, (u32)pick, (const u32*)c->d_block_tallies, n_tally_rows, c->d_counters,
+                               surely_dense ? 1 : 0, c->d_accept_rows, c->d_sumsq_rows, inv_w, sub, sub_log2, n_pass, table_in_lds);
         }
-        {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
+        if (launch_direct) {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
             const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
             hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
-                               c->d_acc[1], c->d_home, (u32)pick, c->d_counters, c->d_accept_rows + ACCEPT_ROWS,
-                               c->d_sumsq_rows + ACCEPT_ROWS, inv_w, sub >= 2 ? 1 : 0);
+                               c->d_acc[1], c->d_home, (u32)pick, (const u32*)c->d_block_tallies, n_tally_rows, c->d_counters,
+                               launch_staged ? 0 : 1, c->d_accept_rows + ACCEPT_ROWS, c->d_sumsq_rows + ACCEPT_ROWS, inv_w,
+                               launch_staged ? 1 : 0);
         }
     }
     LAUNCH_CHECK(c, "apply_arrivals");
-    c->finalized = 0; c->norm_in_mailbox = 0;
+    c->finalized = 0; c->norm_in_mailbox = 0; c->counters_in_mailbox = 0;
     return DBLP_OK;
 }
 
@@ -1809,6 +1848,7 @@ extern "C" int dblp_loss_account(dblp_ctx* c, uint32_t bound_ppm, uint32_t* d_mi
     }
     LAUNCH_CHECK(c, "loss_account");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->mailbox_seen = 1;
     const u64 total = c->h_mailbox[0];
     *h_retx_count = total;
     *h_all_met = total == 0;
@@ -1828,22 +1868,24 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
     const Geo& g = c->g;
     const u64 tiles = ((u64)g.n_pkts + FIN_TILE - 1) / FIN_TILE;
     const u32 work = grid_for(c, (tiles + 3) / 4, FIN_BLOCKS_PER_CU);
-    const u32 grid = work + (c->fold ? 1 : 0);      // folded: one more block sums the gather's rows for Eq. 1
+    const u32 grid = work + 1;      // one more block sums the gather's rows: accepted packets, and the sum of squares for Eq. 1
     float* out = in_place ? c->d_acc[0] : d_out;
     {
         ProfScope ps(c, DBLP_K_FINALIZE);
         const size_t table = ((size_t)g.B + 1) * sizeof(u32);
         void (*kern)(Geo, const u64*, const float*, const float*, uint8_t*, float*, int, float, int, double*, u32,
-                     const double*, u32, double*) = table <= IDX_TABLE_LDS_MAX ? finalize_pass<true> : finalize_pass<false>;
+                     const double*, const u64*, u32, u64*, u64*) = table <= IDX_TABLE_LDS_MAX ? finalize_pass<true> : finalize_pass<false>;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), table <= IDX_TABLE_LDS_MAX ? table : 0, c->stream, g, c->d_bitmap,
                            (const float*)c->d_acc[0], (const float*)c->d_acc[1], c->d_home, out, c->fold ? 0 : 1, (float)g.W,
-                           in_place ? 1 : 0, c->d_partials, work, (const double*)c->d_sumsq_rows, (u32)(2 * ACCEPT_ROWS),
-                           (double*)(c->d_mailbox + 1));
+                           in_place ? 1 : 0, c->d_partials, work, (const double*)c->d_sumsq_rows, (const u64*)c->d_accept_rows,
+                           (u32)(2 * ACCEPT_ROWS), c->d_counters, c->d_mailbox);
     }
     LAUNCH_CHECK(c, "finalize");
     c->n_partials = work;
     c->finalized = 1;
     c->norm_in_mailbox = c->fold;
+    c->counters_in_mailbox = 1;     // valid on the host once the stream has been synchronised (mailbox_seen)
+    c->mailbox_seen = 0;
     return DBLP_OK;
 }
 
@@ -1867,6 +1909,7 @@ extern "C" int dblp_phase_signal(dblp_ctx* c, const float* d_vec, double* h_norm
     }
     LAUNCH_CHECK(c, "phase_signal");
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->mailbox_seen = 1;
     double ss;
     memcpy(&ss, c->h_mailbox + 1, sizeof ss);
     if (ss < 0.0) ss = 0.0;     // the running sum of squares can end a rounding error below zero
@@ -1936,6 +1979,15 @@ extern "C" int dblp_get_bitmap(dblp_ctx* c, uint64_t* d_out) {
 
 extern "C" int dblp_get_counters(dblp_ctx* c, uint64_t h[4]) {
     if (!c || !h) return DBLP_EINVAL;
+    if (c->counters_in_mailbox && c->mailbox_seen) {
+        // the last finalize mirrored the counters into the host mailbox and the stream has been
+        // synchronised since: nothing to launch, nothing to wait for
+        h[0] = c->h_mailbox[8];
+        h[1] = c->h_mailbox[9] - c->h_mailbox[8];
+        h[2] = c->h_mailbox[10];
+        h[3] = c->h_mailbox[11];
+        return DBLP_OK;
+    }
     HIP_TRY(c, hipSetDevice(c->device));
     u64 tmp[C_COUNT];
     hipLaunchKernelGGL(fold_accept_rows, dim3(1), dim3(256), 0, c->stream, c->d_accept_rows, (u32)(2 * ACCEPT_ROWS),

@@ -86,6 +86,9 @@ def _hip_lib():
         lib.dblp_gen_hip_grad_fill.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64,
                                                ctypes.c_uint64, ctypes.c_float, ctypes.c_uint32,
                                                ctypes.c_float, ctypes.c_void_p]
+        lib.dblp_gen_hip_resend_slots.restype = ctypes.c_int
+        lib.dblp_gen_hip_resend_slots.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p,
+                                                  ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
         _hip = lib
     return _hip
 
@@ -124,6 +127,14 @@ def grad_fill_device(d_ptr: int, seed: int, w: int, it: int, e0: int, n: int, si
     """Same values as grad_values(), written by the device generator to device memory."""
     rc = _hip_lib().dblp_gen_hip_grad_fill(d_ptr, e0, n, key(seed, STREAM_GRAD, it, 0, w),
                                            float(grad_scale(sigma)), tail_ppm, tail_mul, stream)
+    if rc != 0:
+        raise RuntimeError(f"device generator launch failed: hipError {rc}")
+
+
+def resend_slots_device(d_list_ptr: int, n: int, d_slot_of_ptr: int, n_pkts: int, d_out_ptr: int, stream: int = 0) -> None:
+    """The simulated sender on the device: out[i] = slot_of[worker_i * n_pkts + seq_i] for the first n
+    entries (worker << 32 | seq) of a retransmit list.  All arguments are device addresses."""
+    rc = _hip_lib().dblp_gen_hip_resend_slots(d_list_ptr, n, d_slot_of_ptr, n_pkts, d_out_ptr, stream)
     if rc != 0:
         raise RuntimeError(f"device generator launch failed: hipError {rc}")
 

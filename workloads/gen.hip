@@ -57,3 +57,27 @@ extern "C" int dblp_gen_hip_grad_fill(float* d_out, uint64_t e0, uint64_t n, uin
                        d_out, e0, n, key, scale, tail_ppm, tail_mul);
     return (int)hipGetLastError();
 }
+
+/* The simulated sender's answer to a retransmit list: entry i = (worker << 32) | seq names a
+   packet, slot_of[worker * n_pkts + seq] is where that packet sits in the wire buffer, and the
+   resent packet is delivered from there (a retransmitted packet is byte-identical to the
+   original).  Input plumbing only. */
+__global__ __launch_bounds__(256) void resend_slots_kernel(const uint64_t* __restrict__ list, uint64_t n,
+                                                           const uint32_t* __restrict__ slot_of, uint64_t n_pkts,
+                                                           uint32_t* __restrict__ out_slots) {
+    uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        uint64_t e = list[i];
+        out_slots[i] = slot_of[(e >> 32) * n_pkts + (e & 0xFFFFFFFFULL)];
+    }
+}
+
+extern "C" int dblp_gen_hip_resend_slots(const uint64_t* d_list, uint64_t n, const uint32_t* d_slot_of,
+                                         uint64_t n_pkts, uint32_t* d_out_slots, void* stream) {
+    if (n == 0) return 0;
+    uint64_t blocks = (n + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(resend_slots_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       d_list, n, d_slot_of, n_pkts, d_out_slots);
+    return (int)hipGetLastError();
+}
