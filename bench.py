@@ -360,7 +360,8 @@ def cpu_baseline(w, target_elems: int) -> dict:
 
 def run_leg(job, w, its, bounds=None, profile=False) -> dict:
     """Times the steps `its` (iteration numbers).  bounds: None = the workload's policy decides, starting
-    from `job.next_bound`; a dict iteration -> bound replays a recorded run (the same work again)."""
+    from `job.next_bound`; a dict iteration -> bound replays a recorded run (the same work again).
+    profile: False, True (every kernel group bracketed by events) or a bit mask of kernel groups."""
     import torch
     from paper_2605_01989_amd import binding
     agg = job.agg
@@ -373,7 +374,7 @@ def run_leg(job, w, its, bounds=None, profile=False) -> dict:
         return sched[t % len(sched) - 1] / sched[t % len(sched)]
 
     if profile:
-        agg.profile_enable(True)
+        agg.profile_enable(profile)
         for k in range(binding.K_FINALIZE + 1):
             agg.profile_read(k)
     torch.cuda.synchronize()
@@ -447,7 +448,8 @@ def main():
     total = args.warmup + args.steps
     n_extra = min(args.extra_steps, args.steps)
     extra_its = list(range(args.warmup, args.warmup + n_extra))
-    job = DeviceJob(w, n_masks=total, place=args.place, order=args.order, queue=args.arrivals == "queue",
+    form = {"queue": True, "tables": False}
+    job = DeviceJob(w, n_masks=total, place=args.place, order=args.order, queue=form[args.arrivals],
                     accumulator=args.accumulator, both_forms_its=extra_its)
     agg = job.agg
 
@@ -464,7 +466,10 @@ def main():
     picks, job.picks = job.picks[:len(job.chunks)], None
     for st in warm["per_step"]:
         log(f"[bench] warmup {st['it']}: bound={st['bound_ppm']} rounds={st['rounds']}")
-    main_leg = run_leg(job, w, list(range(args.warmup, total)), profile=True)
+    from paper_2605_01989_amd import binding
+    # the timed region brackets only the dominant kernel group with events (two event records per
+    # batch); the per-group breakdown comes from a replay of its first steps with every group bracketed
+    main_leg = run_leg(job, w, list(range(args.warmup, total)), profile=1 << binding.K_GATHER)
     wall, prof = main_leg["wall"], main_leg["prof"]
     accepted_total = main_leg["accepted"]
     ms_per_step = wall * 1e3 / args.steps
@@ -500,20 +505,23 @@ def main():
                     path_hbm_frac=round((acc * L.stride + leg["steps"] * 4 * L.N) / leg["wall"] / 1e9 / HBM_PEAK_GBPS, 4))
 
     other = {}
+    breakdown = None
     if n_extra:
         bounds = {st["it"]: st["bound_ppm"] for st in main_leg["per_step"]}
-        ref_leg = dict(main_leg, per_step=main_leg["per_step"][:n_extra])
-        other[f"{args.arrivals}+{args.accumulator} (the timed run, its first {n_extra} steps replayed)"] = \
+        leg = run_leg(job, w, extra_its, bounds, profile=True)
+        breakdown = dict(steps=n_extra, ms_per_step=round(leg["wall"] * 1e3 / n_extra, 3),
+                         **{k: round(v[0] / n_extra, 4) for k, v in leg["prof"].items()})
+        other[f"{args.arrivals}+{args.accumulator} (the timed run, its first {n_extra} steps replayed, no event brackets)"] = \
             leg_summary(run_leg(job, w, extra_its, bounds))
-        job.queue = not job.queue
-        name = "tables" if args.arrivals == "queue" else "queue"
-        other[f"{name}+{args.accumulator}"] = leg_summary(run_leg(job, w, extra_its, bounds))
-        job.queue = not job.queue
+        for name in ("queue", "tables"):
+            if name != args.arrivals:
+                job.queue = form[name]
+                other[f"{name}+{args.accumulator}"] = leg_summary(run_leg(job, w, extra_its, bounds))
+        job.queue = form[args.arrivals]
         if acc_info["copies"] == 2:
             job.use_single_accumulator()
             run_leg(job, w, extra_its[:1], bounds)          # one untimed step on the new copy
             other[f"{args.arrivals}+one"] = leg_summary(run_leg(job, w, extra_its, bounds))
-        del ref_leg
 
     out = dict(metric="aggregated_gradient_GBps", value=round(value, 2), unit="GB/s", n_gpus=1,
                steps=args.steps, warmup=args.warmup, ms_per_step=round(ms_per_step, 3),
@@ -529,7 +537,8 @@ def main():
                path_hbm_frac_counting_a_separate_finalize_pass=round(survey_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),
                retransmission_rounds=main_leg["rounds"], resent_packets=main_leg["resent"],
                gpu_event_ms_per_step=round(main_leg["event_ms"] / args.steps, 3),
-               kernel_ms_per_step={k: round(v[0] / args.steps, 4) for k, v in prof.items()},
+               kernel_ms_per_step=dict(gather=round(g_ms / args.steps, 4)),
+               kernel_ms_per_step_replay_all_groups_bracketed=breakdown,
                sender_side_not_in_value=sender, other_forms=other, per_step=main_leg["per_step"], roofline=roofline)
     if not args.no_cpu_baseline:
         del job

@@ -283,8 +283,9 @@ int dblp_get_counters(dblp_ctx* ctx, uint64_t h_counters[4]);
 int dblp_set_prev_norm(dblp_ctx* ctx, double norm, int have);
 int dblp_get_prev_norm(const dblp_ctx* ctx, double* h_norm, int* h_have);
 
-/* Optional tracing: with profiling on, the launches of the kernels below are bracketed by
- * HIP events on the context's stream.  dblp_profile_read synchronises the stream, returns
+/* Optional tracing: `on` is a bit mask of kernel groups (bit DBLP_K_* set = the launches of that
+ * group are bracketed by HIP events on the context's stream; 0 = off, 15 = all four; a bracket
+ * costs two event records, which shows on small rounds).  dblp_profile_read synchronises the stream, returns
  * the summed duration (milliseconds) and number of launches recorded for one kernel group
  * since the last read of that group, and forgets them.  At most 16384 brackets are kept between
  * reads; further ones are dropped.  dblp_profile_enable may return ENOMEM. */

@@ -275,8 +275,9 @@ class Aggregator:
         self._check(lib().dblp_get_counters(self._h, c))
         return dict(accepted=int(c[0]), duplicate=int(c[1]), stale=int(c[2]), invalid=int(c[3]))
 
-    def profile_enable(self, on: bool):
-        self._check(lib().dblp_profile_enable(self._h, int(on)))
+    def profile_enable(self, on):
+        """on: False/0 off, True all kernel groups, or a bit mask (1 << K_GATHER, ...)."""
+        self._check(lib().dblp_profile_enable(self._h, 15 if on is True else int(on)))
 
     def profile_read(self, kernel: int):
         """(total milliseconds, launches) of one kernel group since the last read."""

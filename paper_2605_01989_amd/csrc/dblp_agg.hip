@@ -1254,7 +1254,7 @@ struct dblp_ctx {
     int round_open; int finalized; uint16_t round;
     double prev_norm; int have_prev;
     // optional per-kernel timing (HIP events on the context's stream)
-    int profiling;
+    int profiling;          // bit k set: launches of kernel group k are bracketed by events
     struct Timed { hipEvent_t a, b; int kernel; };
     std::vector<Timed>* timed;        // recorded, not yet read
     std::vector<hipEvent_t>* ev_pool; // free events
@@ -1272,7 +1272,7 @@ static hipEvent_t prof_event(dblp_ctx* c) {
 struct ProfScope {
     dblp_ctx* c; hipEvent_t a; int kernel;
     ProfScope(dblp_ctx* c_, int kernel_) : c(c_), a(nullptr), kernel(kernel_) {
-        if (c->profiling && (a = prof_event(c))) (void)hipEventRecord(a, c->stream);
+        if (((c->profiling >> kernel) & 1) && (a = prof_event(c))) (void)hipEventRecord(a, c->stream);
     }
     ~ProfScope() {
         if (!a) return;
@@ -1741,10 +1741,11 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
         ProfScope ps(c, DBLP_K_INDEX);
         const u32 grid = grid_for(c, (n_arrivals + 255) / 256, IDX_BLOCKS_PER_CU);
         const size_t table = ((size_t)g.B + 1) * sizeof(u32);
+        const bool lds = table <= IDX_TABLE_LDS_MAX;
         void (*idx)(Geo, const uint8_t*, const uint16_t*, u64, const u64*, const u32*, const u64*, u64, u32, u64*, u32*) =
-            table <= IDX_TABLE_LDS_MAX ? (d_queue ? index_arrivals<true, true> : index_arrivals<true, false>)
-                                       : (d_queue ? index_arrivals<false, true> : index_arrivals<false, false>);
-        hipLaunchKernelGGL(idx, dim3(grid), dim3(256), table <= IDX_TABLE_LDS_MAX ? table : 0, c->stream, g,
+            lds ? (d_queue ? index_arrivals<true, true> : index_arrivals<true, false>)
+                : (d_queue ? index_arrivals<false, true> : index_arrivals<false, false>);
+        hipLaunchKernelGGL(idx, dim3(grid), dim3(256), lds ? table : 0, c->stream, g,
                            (const uint8_t*)d_packets, d_src_worker, (u64)n_slots, (const u64*)d_mask, d_order,
                            (const u64*)d_queue, (u64)n_arrivals, (u32)c->round, c->d_pending, c->d_block_tallies);
         n_tally_rows = grid;
@@ -2014,7 +2015,7 @@ extern "C" int dblp_profile_enable(dblp_ctx* c, int on) {
             return fail(c, DBLP_ENOMEM, "profile_enable: out of host memory");
         }
     }
-    c->profiling = on != 0;
+    c->profiling = on & ((1 << DBLP_K_COUNT) - 1);
     return DBLP_OK;
 }
 
