@@ -29,11 +29,13 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
 BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; later rounds lose nothing
 
-# HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# keyed by the SHA-256 of the kernel source it was measured on; anything else reports null.
-# value = measured bytes / algorithmic bytes per launch on the default workload.
-PMC_TRAFFIC_RATIO: dict[str, float] = {
-    "69352d80a5c626eca24181f95df97d1c64b5d41845050391e76fc1ea62cbda2c": 1.067,   # profiles/receiver_path_cfg5.md
+# HBM traffic of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE x 2.00 + WRITE_SIZE,
+# the factors calibrated on a 1 GiB copy), keyed by the SHA-256 of the kernel source it was measured
+# on and by workload; anything else reports null.
+# value = measured bytes / algorithmic bytes of a first-transmission launch.
+PMC_TRAFFIC_RATIO: dict[tuple[str, str], float] = {
+    ("e59d6fa3cb39fc8d66591983b189c6212b4cdcaf7433eb6930a788a3c14d0017", "cfg5"): 1.067,   # profiles/receiver_path_cfg5.md
+    ("e59d6fa3cb39fc8d66591983b189c6212b4cdcaf7433eb6930a788a3c14d0017", "cfg4"): 1.031,   # profiles/receiver_path_cfg4.md
 }
 
 
@@ -481,7 +483,7 @@ def main():
     g_ms, g_n = prof["gather"]
     g_bytes = accepted_total * L.stride + args.steps * 4 * L.N
     achieved = g_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
-    ratio_pmc = PMC_TRAFFIC_RATIO.get(_kernel_source_hash())
+    ratio_pmc = PMC_TRAFFIC_RATIO.get((_kernel_source_hash(), w.name))
     roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
                     frac=round(achieved / HBM_PEAK_GBPS, 4), kernel="gather_accumulate_staged",
                     launches=g_n, avg_launch_ms=round(g_ms / max(g_n, 1), 4),

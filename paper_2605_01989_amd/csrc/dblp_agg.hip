@@ -4,7 +4,8 @@
 // Data flow of one arrival batch (Alg. "DBLP_RECV", chunk-arrival branch):
 //   index_arrivals   one thread per arrival: header parse, validation, and an atomicMin of
 //                    (arrival rank << 32 | slot) into the arrival index `pending[w][seq]`, so the
-//                    earliest copy of a packet in the batch wins; also the touched seq range
+//                    earliest copy of a packet in the batch wins; per-block tallies (stale, invalid,
+//                    candidates, touched seq range) that every gather block adds up for itself
 //   gather_accumulate_staged / gather_accumulate
 //                    organised by OUTPUT packet: a block takes a group of consecutive sequence
 //                    numbers, reads the index entries of all workers, drops copies of packets
@@ -43,7 +44,7 @@ typedef uint32_t u32;
 #define WAVE 64
 
 // device counters (u64 each)
-enum { C_ACCEPTED = 0, C_BATCH_CAND, C_STALE, C_INVALID, C_CANDIDATES, C_LO, C_HI, C_PKT_BAD, C_COUNT };
+enum { C_ACCEPTED = 0, C_STALE, C_INVALID, C_CANDIDATES, C_PKT_BAD, C_COUNT };
 
 struct Geo {
     const u32* first_seq;   // [B+1]
@@ -163,7 +164,7 @@ __global__ __launch_bounds__(256) void fill_u64(u64* __restrict__ p, u64 n, u64 
 __global__ void reset_counters(u64* __restrict__ c) {
     u32 t = threadIdx.x;
     if (t >= C_COUNT) return;
-    c[t] = t == C_LO ? NONE64 : 0;
+    c[t] = 0;
 }
 
 // Start of a round in one launch: bitmap and the gather kernels' per-block rows to zero, counters reset.
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(256) void reset_round(u64* __restrict__ bitmap, u64
     for (u64 i = (u64)blockIdx.x * blockDim.x + threadIdx.x; i < n_bitmap + n_rows; i += stride) {
         if (i < n_bitmap) bitmap[i] = 0; else rows[i - n_bitmap] = 0;
     }
-    if (blockIdx.x == 0 && threadIdx.x < C_COUNT) counters[threadIdx.x] = threadIdx.x == C_LO ? NONE64 : 0;
+    if (blockIdx.x == 0 && threadIdx.x < C_COUNT) counters[threadIdx.x] = 0;
 }
 
 // counters[C_ACCEPTED] = sum of the per-block rows written by the gather kernels.  One block.
