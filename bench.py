@@ -81,7 +81,10 @@ class DeviceJob:
         t0 = time.time()
         self.packets = torch.empty(self.n_slots * L.stride, dtype=torch.uint8, device=dev)
         self.src = torch.empty(self.n_slots, dtype=torch.int16, device=dev)
-        self.d_out = self.agg.accumulator_tensor(0)
+        # W a power of two: the result is left in place (d_out is a view of the first accumulator copy);
+        # otherwise the library has to divide, which it does into a buffer of the caller's
+        self.in_place = (L.W & (L.W - 1)) == 0
+        self.d_out = self.agg.accumulator_tensor(0) if self.in_place else torch.empty(L.N, dtype=torch.float32, device=dev)
         self.d_missing = torch.empty(L.W * L.B, dtype=torch.int32, device=dev)
         self.list_cap = max(self.n_slots // 8, 1 << 16)
         self.d_list = torch.empty(self.list_cap, dtype=torch.int64, device=dev)
@@ -223,7 +226,10 @@ class DeviceJob:
         """Switch the context to one accumulator copy (d_out is a view of it: refreshed here)."""
         self.d_out = None
         self.agg.accumulator_copies(1)
-        self.d_out = self.agg.accumulator_tensor(0)
+        # W a power of two: the result is left in place (d_out is a view of the first accumulator copy);
+        # otherwise the library has to divide, which it does into a buffer of the caller's
+        self.in_place = (L.W & (L.W - 1)) == 0
+        self.d_out = self.agg.accumulator_tensor(0) if self.in_place else torch.empty(L.N, dtype=torch.float32, device=dev)
 
     # -- the timed path --------------------------------------------------------------------
     def step(self, it: int, bound_ppm: int, scale_ratio: float = 1.0, record: list | None = None) -> dict:
@@ -275,7 +281,7 @@ class DeviceJob:
                     resent = None          # survivors not counted here: the caller derives them from the accepted counter
                 elif resent is not None:
                     resent += count        # a round without drawn loss: everything arrives
-        agg.finalize(None)        # in place: the result is d_out, the first accumulator copy
+        agg.finalize(None if self.in_place else self.d_out)     # in place: the result is the first accumulator copy
         prev = agg.get_prev_norm()
         if prev is not None:
             agg.set_prev_norm(prev * scale_ratio)
@@ -532,7 +538,8 @@ def main():
                                     f"packets/round={L.W * L.n_pkts} loss={w.loss['kind']} "
                                     f"policy={w.policy['kind']}",
                            placement=job.place, arrival_order=job.order, arrivals=args.arrivals,
-                           accumulator=acc_info, result="in place (first accumulator copy)",
+                           accumulator=acc_info,
+                           result="in place (first accumulator copy)" if job.in_place else "written to a separate buffer",
                            chunk_steps=len(job.chunks), resident_packet_GB=round(job.packets.numel() / 1e9, 2)),
                packets_per_s=round(accepted_total / wall, 1),
                path_hbm_frac=round(path_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),

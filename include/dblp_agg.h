@@ -36,6 +36,11 @@
  * one short; packets never straddle buckets.  Sequence numbers run bucket-major
  * from 0 to n_pkts - 1 for every worker.
  *
+ * Limits: at most DBLP_MAX_WORKERS (64) workers; fewer than 2^32 - 1 packets per worker and
+ * round, slots per packet buffer and arrivals per batch; payloads of 1..65535 floats; a
+ * bucket holds fewer than 2^32 elements; N itself is a 64-bit count.  Anything beyond is
+ * refused with DBLP_EINVAL at dblp_create or at the call.
+ *
  * Wire packet (Sec. "Metadata": sequence number, round counter, data length;
  * field widths are this library's choice), little-endian, `stride` bytes apart
  * with stride = 8 + 4P rounded up to 16:

@@ -215,3 +215,48 @@ def test_full_size_sampled_buckets_and_global_properties(name, BOUND_PPM, extra)
     _SURVIVE.clear()
     del job, bitmap, bitmap2, first_out
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("rate,fixed_rounds,dblp_rounds", [(0.6, (8, 10), (1, 1)), (0.9, (43, 49), (8, 8))])
+def test_microburst_study_rounds_at_model_size_match_the_oracle(rate, fixed_rounds, dblp_rounds):
+    """study_microburst.py's figures at the size it runs (EfficientNetB0-sized gradient, 3 workers,
+    one accounting unit per worker, whole-iteration burst loss on every retransmission round): the
+    number of retransmission rounds and every probe's counts and list, under the fixed tolerance
+    and under P_high, must be what the oracle's header-only receiver gets from the same draws."""
+    import bench
+    import oracle
+    w = wl.paper_model_workload("effnetb0", rate, burst_iters=(1,), iterations=3)
+    L = w.layout
+    job = bench.DeviceJob(w, n_masks=3, per_iteration_retx=True)
+    n_slots = L.W * L.n_pkts
+    o = oracle.Oracle(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt)
+    headers = np.empty(n_slots * 8, dtype=np.uint8)
+    src = np.empty(n_slots, dtype=np.uint16)
+    for wk in range(L.W):
+        o.write_headers(wk, job.rnd_id, 0, L.n_pkts, headers, src, slot_map=job.slot_of[wk])
+    order = wl.arrival_order(job.order, n_slots, w.seed, 0)
+    seen = {}
+    for it, bound in ((0, w.policy["low_ppm"]), (1, w.policy["low_ppm"]), (1, w.policy["high_ppm"]), (2, w.policy["high_ppm"])):
+        probes = []
+        res = job.step(it, bound, record=probes)
+        o.begin_round(job.rnd_id)
+        mask = wl.slot_mask_words(w.survive(it, 0, job.slot_of), job.slot_of)
+        o.apply_arrivals(headers, src, n_slots, mask, order, n_slots, accumulate=False, stride=8)
+        for rnd, pr in enumerate(probes):
+            missing, lst, count, met = o.loss_account(bound)
+            assert (count, met) == (pr["count"], pr["met"]) and np.array_equal(missing, pr["missing"])
+            assert np.array_equal(lst, pr["list"]), f"iteration {it}, probe {rnd}: retransmit list differs"
+            if met:
+                break
+            ok = w.survive(it, rnd + 1, job.slot_of)[(lst >> np.uint64(32)).astype(np.int64),
+                                                     (lst & np.uint64(0xFFFFFFFF)).astype(np.int64)].astype(bool)
+            slots = job.slot_of[(lst >> np.uint64(32)).astype(np.int64), (lst & np.uint64(0xFFFFFFFF)).astype(np.int64)][ok]
+            o.apply_arrivals(headers, src, n_slots, None, slots.astype(np.uint32), slots.size, accumulate=False, stride=8)
+        assert o.counters() == job.agg.get_counters()
+        assert res["rounds"] == len(probes) - 1
+        seen[(it, bound)] = res["rounds"]
+    lo, hi = w.policy["low_ppm"], w.policy["high_ppm"]
+    assert fixed_rounds[0] <= seen[(1, lo)] <= fixed_rounds[1], seen      # the burst iteration under the fixed tolerance
+    assert dblp_rounds[0] <= seen[(1, hi)] <= dblp_rounds[1], seen        # ... and under P_high = p + 40 %
+    assert seen[(0, lo)] <= 2 and seen[(2, hi)] == 0, seen                # quiet iterations
+    record_stat(f"microburst_rounds_rate_{rate}", dict(rounds={f"{k[0]}@{k[1]}": v for k, v in seen.items()}))
