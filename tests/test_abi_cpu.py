@@ -55,6 +55,25 @@ def test_null_context_calls_return_einval_without_a_gpu():
     assert L.dblp_begin_round(None, 1) == binding.EINVAL
     assert L.dblp_destroy(None) == binding.OK
     assert L.dblp_layout(None, None, None, None) == binding.EINVAL
+    assert L.dblp_accumulator_ptr(None, 0, None) == binding.EINVAL
+    # the context-free entry point checks its arguments before it touches the device
+    assert L.dblp_sumsq_static(0, None, None, 10, None) == binding.EINVAL
+    assert b"null pointer" in L.dblp_sumsq_static_error()
+    assert L.dblp_sumsq_static(99, None, None, 10, None) == binding.EINVAL
+    assert b"device ordinal" in L.dblp_sumsq_static_error()
+
+
+def test_create_refuses_a_bad_accumulator_configuration_without_a_gpu():
+    """The configuration is validated before any device call."""
+    import ctypes
+    arr = (binding._Bucket * 1)(binding._Bucket(0, 100))
+    for kw in (dict(mode=3), dict(mode=0, fraction=0.95), dict(mode=0, seconds=-1.0), dict(mode=2, acc0=256),
+               dict(mode=0, acc0=257), dict(mode=1, acc0=256, acc1=256), dict(mode=0, acc0=256, acc1=512)):
+        acc = (ctypes.c_void_p * 2)(kw.get("acc0"), kw.get("acc1"))
+        cfg = binding._Config(2, 10, 100, 1, arr, 0.5, 0, None, kw["mode"], acc, kw.get("fraction", 0.0), kw.get("seconds", 0.0))
+        h = ctypes.c_void_p()
+        assert dblp.lib().dblp_create(ctypes.byref(h), ctypes.byref(cfg)) == binding.EINVAL, kw
+        assert not h.value
 
 
 def test_epoch_controller_matches_oracle_trace_and_starts_low():
