@@ -224,12 +224,11 @@ class DeviceJob:
 
     def use_single_accumulator(self):
         """Switch the context to one accumulator copy (d_out is a view of it: refreshed here)."""
-        self.d_out = None
+        if self.in_place:
+            self.d_out = None                 # the view of the copy that is about to be released
         self.agg.accumulator_copies(1)
-        # W a power of two: the result is left in place (d_out is a view of the first accumulator copy);
-        # otherwise the library has to divide, which it does into a buffer of the caller's
-        self.in_place = (L.W & (L.W - 1)) == 0
-        self.d_out = self.agg.accumulator_tensor(0) if self.in_place else torch.empty(L.N, dtype=torch.float32, device=dev)
+        if self.in_place:
+            self.d_out = self.agg.accumulator_tensor(0)
 
     # -- the timed path --------------------------------------------------------------------
     def step(self, it: int, bound_ppm: int, scale_ratio: float = 1.0, record: list | None = None) -> dict:
