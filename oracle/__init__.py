@@ -78,6 +78,7 @@ class Oracle:
             raise ValueError("oracle_create rejected the configuration")
         self.n_pkts = int(lib().oracle_n_pkts(self._h))
         self.stride = (8 + 4 * self.P + 15) // 16 * 16
+        self._prev = None      # the stored previous norm, as last set or computed (for reporting only)
 
     def close(self):
         if self._h:
@@ -155,10 +156,15 @@ class Oracle:
         assert out.size == self.N
         norm, delta, crit = ctypes.c_double(), ctypes.c_double(), ctypes.c_int()
         lib().oracle_phase_signal(self._h, _p(out), ctypes.byref(norm), ctypes.byref(delta), ctypes.byref(crit))
+        self._prev = norm.value
         return norm.value, delta.value, bool(crit.value)
 
     def set_prev_norm(self, v: float | None):
         lib().oracle_set_prev_norm(self._h, 0.0 if v is None else float(v), int(v is not None))
+        self._prev = v
+
+    def get_prev_norm(self):
+        return self._prev
 
     def received(self) -> np.ndarray:
         out = np.empty((self.W, self.n_pkts), dtype=np.uint8)

@@ -118,6 +118,9 @@ class OracleRx:
     def phase_signal(self):
         return self.o.phase_signal(self.out)
 
+    def prev_norm(self):
+        return self.o.get_prev_norm()
+
     def bitmap(self):
         return self.o.received()
 
@@ -143,9 +146,10 @@ def run_iteration(rx, sc: Scenario, bound_ppm: int, max_rounds: int = 256) -> di
         slots = sc.resend(lst, rnd)
         rx.apply(0, L.W * L.n_pkts, None, slots, slots.size)
     out = rx.finalize()
+    prev = rx.prev_norm()
     norm, delta, crit = rx.phase_signal()
     return dict(probes=probes, rounds=rnd, bitmap=rx.bitmap(), out=out, norm=norm, rel_delta=delta,
-                critical=crit, counters=rx.counters())
+                critical=crit, counters=rx.counters(), prev_norm=prev)
 
 
 def definition_mean(sc: Scenario, received: np.ndarray) -> np.ndarray:
@@ -276,6 +280,9 @@ class GpuRx:
     def phase_signal(self):
         return self.agg.phase_signal()
 
+    def prev_norm(self):
+        return self.agg.get_prev_norm()
+
     def bitmap(self):
         L = self.sc.L
         self.agg.get_bitmap(self.d_bitmap)
@@ -322,7 +329,8 @@ def record_stat(name: str, stats: dict) -> None:
 
 def compare_results(got: dict, ref: dict, sc: Scenario) -> dict:
     """Integer outputs bit-exact; floats within FLOAT_TOL of the oracle relative to the addends'
-    magnitude; never-received elements exactly zero; norm within 1e-6."""
+    magnitude; never-received elements exactly zero; norm within 1e-6 of itself plus four fp32
+    ulps of the addends' magnitude (in the 2-norm)."""
     assert np.array_equal(got["bitmap"], ref["bitmap"]), "bitmap differs"
     assert got["rounds"] == ref["rounds"]
     assert len(got["probes"]) == len(ref["probes"])
@@ -341,10 +349,28 @@ def compare_results(got: dict, ref: dict, sc: Scenario) -> dict:
     nz = r != 0
     plain = err[nz] / np.abs(r[nz])
     assert got["critical"] == ref["critical"]
+    norm_tol = 0.0
     if ref["norm"] > 0:
-        assert abs(got["norm"] - ref["norm"]) <= 1e-6 * ref["norm"], (got["norm"], ref["norm"])
+        # | ||gpu|| - ||oracle|| | <= ||gpu - oracle||_2: besides 1e-6 of the norm itself the fp32 result may
+        # carry a few ulps of its ADDENDS' magnitude per element (the same cancellation that makes the
+        # plain element-wise relative error meaningless: a one-element gradient whose 48 addends of
+        # 1e-3 cancel to 3e-6 has a norm that is exact only to 4e-6 of itself)
+        norm_tol = 1e-6 * ref["norm"] + 2.0 ** -22 * float(np.linalg.norm(scale))
+        assert abs(got["norm"] - ref["norm"]) <= norm_tol, (got["norm"], ref["norm"], norm_tol)
+    # Eq. 1 on each side's own norms: the reported change must be |prev - cur| / prev of the norms
+    # that side holds; the two sides' values then differ by no more than their norms explain
+    for side in (got, ref):
+        p = side.get("prev_norm")
+        if p:
+            want = abs(p - side["norm"]) / p
+            assert abs(side["rel_delta"] - want) <= 1e-12 * max(1.0, want), (side["rel_delta"], want)
+        else:
+            assert np.isinf(side["rel_delta"]) and side["critical"]
     if np.isfinite(ref["rel_delta"]):
-        assert abs(got["rel_delta"] - ref["rel_delta"]) <= 1e-5
+        slack = norm_tol / ref["norm"] if ref["norm"] > 0 else 0.0
+        if got.get("prev_norm") and ref.get("prev_norm"):
+            slack += abs(got["prev_norm"] - ref["prev_norm"]) / ref["prev_norm"]
+        assert abs(got["rel_delta"] - ref["rel_delta"]) <= 1e-5 + 2.0 * (1.0 + ref["rel_delta"]) * slack
     else:
         assert got["rel_delta"] == ref["rel_delta"]
     return dict(rel_to_addends=rel, rel_to_max=float(err.max() / max(np.abs(r).max(), 1e-300)),
