@@ -661,10 +661,18 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
 #ifndef GS_READERS
 #define GS_READERS 8
 #endif
+#ifndef GS_READERS_SHORT
+#define GS_READERS_SHORT 4            // reader waves and blocks per CU for packets of up to 2 KB
+#endif
+#ifndef GS_MAX_PER_CU_SHORT
+#define GS_MAX_PER_CU_SHORT 3
+#endif
+#ifndef GS_LDS_BUDGET
 #define GS_LDS_BUDGET (48u * 1024u)   // bytes for the two packet buffers
+#endif
 #ifndef GS_MAX_PER_CU
-#define GS_MAX_PER_CU 2               // blocks per CU: measured best for 1.5 KB and 4 KB packets (more waves
-#endif                                // in flight only spread the DRAM accesses over more open rows)
+#define GS_MAX_PER_CU 2               // blocks per CU for packets longer than 2 KB (more waves in flight
+#endif                                // only spread the DRAM accesses over more open rows); see apply_batch
 
 // Sum of one whole packet over the workers in `sub`: lane l holds 16-byte units l, l+64, ...
 // (NP of them).  All NP loads of one worker's packet are issued together, so a packet's
@@ -1776,10 +1784,15 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             if (table_in_lds) lds += table;
             const u64 groups = ((u64)g.n_pkts + sub - 1) / sub;
             const u32 n_pass = (g.units + WAVE - 1) / WAVE;
-            const u32 readers = sub < GS_READERS ? sub : GS_READERS;   // a reader wave takes whole packets
+            // Block shape: packets of up to 2 KB (one or two 1 KB passes) go fastest with 4 reader waves
+            // and three blocks per CU (measured: 5 % off the launch with 8 workers, 0.6 % with 32);
+            // longer packets with up to 8 reader waves and two blocks per CU (three: 9 % slower at 4 KB).
+            const u32 readers_max = n_pass <= 2 ? (u32)GS_READERS_SHORT : (u32)GS_READERS;
+            const u32 per_cu_max = n_pass <= 2 ? (u32)GS_MAX_PER_CU_SHORT : (u32)GS_MAX_PER_CU;
+            const u32 readers = sub < readers_max ? sub : readers_max;   // a reader wave takes whole packets
             u32 per_cu = (u32)((160u * 1024u) / (lds + 1024));
             if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
-            if (per_cu > GS_MAX_PER_CU) per_cu = GS_MAX_PER_CU;
+            if (per_cu > per_cu_max) per_cu = per_cu_max;
             if (per_cu < 1) per_cu = 1;
             void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u32*, u32, u64*, int, u64*, double*, float, u32, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
