@@ -34,8 +34,8 @@ BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; late
 # on and by workload; anything else reports null.
 # value = measured bytes / algorithmic bytes of a first-transmission launch.
 PMC_TRAFFIC_RATIO: dict[tuple[str, str], float] = {
-    ("e59d6fa3cb39fc8d66591983b189c6212b4cdcaf7433eb6930a788a3c14d0017", "cfg5"): 1.067,   # profiles/receiver_path_cfg5.md
-    ("e59d6fa3cb39fc8d66591983b189c6212b4cdcaf7433eb6930a788a3c14d0017", "cfg4"): 1.031,   # profiles/receiver_path_cfg4.md
+    ("ad5c8e0e5e9fde1fb1d0e071cd149a1c7098fb13d75bc391031524bf458121dc", "cfg5"): 1.066,   # profiles/receiver_path_cfg5.md
+    ("ad5c8e0e5e9fde1fb1d0e071cd149a1c7098fb13d75bc391031524bf458121dc", "cfg4"): 1.030,   # profiles/receiver_path_cfg4.md
 }
 
 
