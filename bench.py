@@ -441,7 +441,7 @@ def main():
                          "to that many bytes of first transmissions; about 10 s of single-threaded work)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (all workers are simulated in that GPU's "
+        sys.exit("bench.py: this library runs on one GPU only (all workers are simulated in that GPU's "
                  "memory); --gpus must be 1")
 
     import torch
@@ -498,7 +498,7 @@ def main():
     # mean and the sum of squares are formed in the same pass and the result is left in place, so the
     # compensation pass adds no bytes of its own beyond the spans it zeroes or moves.
     path_bytes = g_bytes
-    survey_bytes = g_bytes + args.steps * 8 * L.N     # what a separate read-scale-write finalize pass would add
+    separate_pass_bytes = g_bytes + args.steps * 8 * L.N     # what a separate read-scale-write finalize pass would add
     acc_info = agg.accumulator_info()
     acc_info.pop("last_pick")
     acc_info["mode"] = args.accumulator
@@ -542,7 +542,7 @@ def main():
                            chunk_steps=len(job.chunks), resident_packet_GB=round(job.packets.numel() / 1e9, 2)),
                packets_per_s=round(accepted_total / wall, 1),
                path_hbm_frac=round(path_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),
-               path_hbm_frac_counting_a_separate_finalize_pass=round(survey_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),
+               path_hbm_frac_counting_a_separate_finalize_pass=round(separate_pass_bytes / wall / 1e9 / HBM_PEAK_GBPS, 4),
                retransmission_rounds=main_leg["rounds"], resent_packets=main_leg["resent"],
                gpu_event_ms_per_step=round(main_leg["event_ms"] / args.steps, 3),
                kernel_ms_per_step=dict(gather=round(g_ms / args.steps, 4)),

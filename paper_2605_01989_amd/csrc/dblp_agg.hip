@@ -547,13 +547,14 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
                                                                     const u32* __restrict__ block_tallies, u32 n_tally_rows,
                                                                     u64* __restrict__ counters, int tally_owner,
                                                                     u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows,
-                                                                    float inv_w, int only_if_sparse) {
-    extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB]
+                                                                    float inv_w, int only_if_sparse, u32 table_in_lds) {
+    extern __shared__ u32 sh_slot[];           // [W rounded up to 4][SUB], then the bucket boundaries when table_in_lds
     __shared__ u64 sh_elem[SUB];
-    __shared__ u32 sh_len[SUB];
+    __shared__ u32 sh_len[SUB], sh_home[SUB];
     __shared__ u32 sh_new[GA_WAVES], sh_old[GA_WAVES];
     __shared__ double sh_sq[GA_WAVES];
     __shared__ u32 sh_tally[GA_WAVES * 5];
+    __shared__ u32 sh_mask[2][2];
     const BatchInfo bi = fold_index_tallies(block_tallies, n_tally_rows, counters, tally_owner && blockIdx.x == 0, sh_tally);
     const u64 lo = bi.lo, hi = bi.hi;
     if (hi == 0) return;                                    // no candidate in this batch
@@ -562,11 +563,63 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
     const u32 wave = threadIdx.x / WAVE;
     const u32 W = g.W;
     const u32 s_lane = lane & (SUB - 1), w_sub = lane / SUB;   // packet and worker-within-load of this lane
-    const u32 grp_end = (u32)((hi + SUB - 1) / SUB);
+    const u32 grp_lo = (u32)(lo / SUB), grp_end = (u32)((hi + SUB - 1) / SUB);
     u32 accepted = 0;
     double sq = 0.0;      // change of the sum of squares of the stored values caused by this lane's writes
+    // bucket boundaries in LDS when the host made room for them: the span lookup is a chain of
+    // dependent loads that every packet of a small batch would wait for
+    const u32* fs = g.first_seq;
+    if (table_in_lds) {
+        u32* tab = sh_slot + (W + 3) / 4 * 4 * SUB;
+        for (u32 i = threadIdx.x; i <= g.B; i += blockDim.x) tab[i] = g.first_seq[i];
+        fs = tab;
+        __syncthreads();
+    }
 
-    for (u32 grp = (u32)(lo / SUB) + blockIdx.x; grp < grp_end; grp += gridDim.x) {
+    // Every block walks the groups of the touched range grid-stride.  When most groups hold no
+    // arrival at all (a small retransmission batch spread over the round: fewer than one candidate
+    // per four groups), the block first looks through the arrival index of up to 64 of its groups at
+    // a time, one wave per group and all loads in flight together, and then walks only the groups
+    // that hold an entry.
+    const bool skim = bi.cand * (4 * SUB) < hi - lo;
+    u32 grp_next = grp_lo + blockIdx.x;
+    u32 tile_base = 0, tile_no = 0;
+    u64 tile_mask = 0;
+    for (;;) {
+        u32 grp;
+        if (skim) {      // block-uniform control flow throughout: the barriers below are reached by all
+            while (tile_mask == 0 && grp_next < grp_end) {
+                u32* mask = sh_mask[tile_no & 1];      // two buffers: the next look clears one while this one is read
+                ++tile_no;
+                tile_base = grp_next;                  // group k of the tile is tile_base + k * gridDim.x
+                const u32 left = (grp_end - grp_next + gridDim.x - 1) / gridDim.x;
+                const u32 n_g = left < 64 ? left : 64;
+                grp_next = left <= 64 ? grp_end : grp_next + 64 * gridDim.x;
+                if (threadIdx.x < 2) mask[threadIdx.x] = 0;
+                __syncthreads();
+                u32 m0 = 0, m1 = 0;
+                for (u32 k = wave; k < n_g; k += GA_WAVES) {
+                    const u32 seq_k = (tile_base + k * gridDim.x) * SUB + s_lane;
+                    bool any = false;
+                    #pragma unroll 4
+                    for (u32 w0 = 0; w0 < W; w0 += 4) {
+                        const u32 w = w0 + w_sub;
+                        if (w < W && seq_k < g.n_pkts) any |= pending[(u64)w * g.n_pkts + seq_k] != NONE64;
+                    }
+                    if (__ballot(any)) { if (k < 32) m0 |= 1u << k; else m1 |= 1u << (k - 32); }
+                }
+                if (lane == 0 && (m0 | m1)) { atomicOr(&mask[0], m0); atomicOr(&mask[1], m1); }
+                __syncthreads();
+                tile_mask = (u64)mask[0] | ((u64)mask[1] << 32);
+            }
+            if (tile_mask == 0) break;
+            grp = tile_base + (u32)__builtin_ctzll(tile_mask) * gridDim.x;
+            tile_mask &= tile_mask - 1;
+        } else {
+            grp = grp_next;
+            if (grp >= grp_end) break;
+            grp_next += gridDim.x;
+        }
         const u32 seq0 = grp * SUB;
         const u32 seq_l = seq0 + s_lane;
         const u32 word = seq0 >> 6, shift = seq0 & 63;
@@ -596,10 +649,11 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
             accepted += (u32)__popcll(nb);
         }
         if (wave == GA_WAVES - 1 && lane < SUB && seq_l < g.n_pkts) {
-            const u32 b = find_bucket(g.first_seq, g.B, seq_l);
-            u64 elem; u32 len;
-            packet_span(g, seq_l, b, &elem, &len);
-            sh_elem[lane] = elem; sh_len[lane] = len;
+            const u32 hm = home[seq_l];                      // only meaningful (and only used) for spans written before
+            const u32 b = find_bucket(fs, g.B, seq_l);
+            const u64 start = (u64)(seq_l - fs[b]) * g.P;    // packet_span with the boundary from the table at hand
+            const u64 left = g.b_cnt[b] - start;
+            sh_elem[lane] = g.b_off[b] + start; sh_len[lane] = left < g.P ? (u32)left : g.P; sh_home[lane] = hm;
         }
         if (lane == 0) { sh_new[wave] = new_or; sh_old[wave] = old_or; }
         __syncthreads();
@@ -616,7 +670,7 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
             const u64 sub = __ballot(slot32 != NONE32);
             const u32 units = (len + 2 + 3) >> 2;            // 16-byte units holding header + payload
             u32 h = pick;
-            if (rmw) h = home[seq0 + t];
+            if (rmw) h = sh_home[t];
             else if (lane == 0) home[seq0 + t] = (uint8_t)pick;
             float* dst0 = (h ? acc1 : acc0) + elem - 2;      // float position i of the packet -> dst0[i]
             for (u32 u0 = 0; u0 < units; u0 += WAVE) {
@@ -1011,15 +1065,16 @@ __device__ __forceinline__ u32 div_small(u32 x, u32 P, float inv_p) {
 // move_home set (in-place form) the entries of moved spans are reset to copy 0.
 // With scale_mode 1 the per-block sums of out^2 go to partials[blockIdx.x].  Otherwise the sum of
 // squares is already known: the gather kernels kept it per block in sumsq_rows, and the one extra
-// block of this launch (blockIdx.x == n_work_blocks) adds those rows up in a fixed order and
-// writes the total to the host mailbox.
+// block of this launch (blockIdx.x == n_work_blocks) adds those rows up in a fixed order (fixed
+// for given launch sizes of the round's gather kernels) and writes the total to the host mailbox.
 template <bool TABLE_IN_LDS>
 __global__ __launch_bounds__(256) void finalize_pass(Geo g, const u64* __restrict__ bitmap, const float* acc0,
                                                      const float* acc1, uint8_t* __restrict__ home,
                                                      float* out, int scale_mode, float wf, int move_home,
                                                      double* __restrict__ partials, u32 n_work_blocks,
                                                      const double* __restrict__ sumsq_rows, const u64* __restrict__ accept_rows,
-                                                     u32 n_rows, u64* __restrict__ counters, u64* __restrict__ mailbox) {
+                                                     u32 rows_staged, u32 rows_direct, u32 row_pitch,
+                                                     u64* __restrict__ counters, u64* __restrict__ mailbox) {
     __shared__ double wsum[4];
     __shared__ u64 asum[4];
     extern __shared__ u32 fs_lds[];             // bucket boundaries (B + 1 words) when TABLE_IN_LDS
@@ -1030,9 +1085,26 @@ __global__ __launch_bounds__(256) void finalize_pass(Geo g, const u64* __restric
         // packets), and the round's counters mirrored into the host mailbox:
         // mailbox[1] = sum of squares (when the gather kept it), mailbox[8..11] = accepted,
         // candidates, stale, invalid
+        // Only the rows that a launch of this round can have written are read: rows_staged of the
+        // staged kernel's, rows_direct of the direct kernel's (row_pitch apart); the rest are zero.
         double s = 0.0;
         u64 a = 0;
-        for (u32 i = threadIdx.x; i < n_rows; i += 256) { s += sumsq_rows[i]; a += accept_rows[i]; }
+        for (u32 k = 0; k < 2; ++k) {
+            const double* sr = sumsq_rows + (size_t)k * row_pitch;
+            const u64* ar = accept_rows + (size_t)k * row_pitch;
+            const u32 n = k ? rows_direct : rows_staged;
+            for (u32 i0 = 0; i0 < n; i0 += 4 * 256) {      // four independent loads of each kind in flight
+                double sv[4]; u64 av[4];
+                #pragma unroll
+                for (u32 j = 0; j < 4; ++j) {
+                    const u32 i = i0 + j * 256 + threadIdx.x;
+                    sv[j] = i < n ? sr[i] : 0.0;
+                    av[j] = i < n ? ar[i] : 0ull;
+                }
+                #pragma unroll
+                for (u32 j = 0; j < 4; ++j) { s += sv[j]; a += av[j]; }
+            }
+        }
         s = wave_sum_f64(s);
         const u32 a_lo = wave_reduce<OpAdd>((u32)(a & 0xFFFFFu)), a_hi = wave_reduce<OpAdd>((u32)(a >> 20));   // 64 x 2^20 fits 32 bits
         if (lane == 0) { wsum[wave_in_block] = s; asum[wave_in_block] = ((u64)a_hi << 20) + a_lo; }
@@ -1253,6 +1325,7 @@ struct dblp_ctx {
     u32* d_need; u32* d_missing; u64* d_offs; double* d_partials;
     u32* d_block_tallies;   // [IDX_BLOCKS_PER_CU * n_cus][5], written by index_arrivals
     u64* d_accept_rows;     // [2][ACCEPT_ROWS] accepted packets per gather block (staged grid, direct grid)
+    u32 rows_used[2];       // largest staged / direct gather grid launched in the open round
     double* d_sumsq_rows;   // [2][ACCEPT_ROWS] sum of squares of what each gather block stored (same allocation)
     u64* h_mailbox;         // pinned host memory, 16 x u64, also mapped into the device
     u64* d_mailbox;         // device address of h_mailbox
@@ -1645,6 +1718,7 @@ extern "C" int dblp_begin_round(dblp_ctx* c, uint16_t round) {
                        c->d_bitmap, n, c->d_accept_rows, (u64)(4 * ACCEPT_ROWS), c->d_counters);
     LAUNCH_CHECK(c, "begin_round");
     c->round = round; c->round_open = 1; c->finalized = 0; c->norm_in_mailbox = 0; c->counters_in_mailbox = 0;
+    c->rows_used[0] = c->rows_used[1] = 0;
     return DBLP_OK;
 }
 
@@ -1798,19 +1872,26 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
-            hipLaunchKernelGGL(kern, dim3(grid_for(c, groups, per_cu)), dim3((readers + 1) * WAVE),
+            const u32 grid = grid_for(c, groups, per_cu);
+            if (grid > c->rows_used[0]) c->rows_used[0] = grid;
+            hipLaunchKernelGGL(kern, dim3(grid), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
                                c->d_acc[1], c->d_home, (u32)pick, (const u32*)c->d_block_tallies, n_tally_rows, c->d_counters,
                                surely_dense ? 1 : 0, c->d_accept_rows, c->d_sumsq_rows, inv_w, sub, sub_log2, n_pass, table_in_lds);
         }
         if (launch_direct) {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
-            const size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
-            hipLaunchKernelGGL(gather_accumulate, dim3(grid_for(c, groups, GA_BLOCKS_PER_CU)), dim3(GA_WAVES * WAVE),
+            size_t lds = (size_t)((g.W + 3) / 4 * 4) * SUB * sizeof(u32);
+            const size_t table = ((size_t)g.B + 1) * sizeof(u32);
+            const u32 table_in_lds = table <= IDX_TABLE_LDS_MAX ? 1u : 0u;
+            if (table_in_lds) lds += table;
+            const u32 grid = grid_for(c, groups, GA_BLOCKS_PER_CU);
+            if (grid > c->rows_used[1]) c->rows_used[1] = grid;
+            hipLaunchKernelGGL(gather_accumulate, dim3(grid), dim3(GA_WAVES * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
                                c->d_acc[1], c->d_home, (u32)pick, (const u32*)c->d_block_tallies, n_tally_rows, c->d_counters,
                                launch_staged ? 0 : 1, c->d_accept_rows + ACCEPT_ROWS, c->d_sumsq_rows + ACCEPT_ROWS, inv_w,
-                               launch_staged ? 1 : 0);
+                               launch_staged ? 1 : 0, table_in_lds);
         }
     }
     LAUNCH_CHECK(c, "apply_arrivals");
@@ -1889,11 +1970,11 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
         ProfScope ps(c, DBLP_K_FINALIZE);
         const size_t table = ((size_t)g.B + 1) * sizeof(u32);
         void (*kern)(Geo, const u64*, const float*, const float*, uint8_t*, float*, int, float, int, double*, u32,
-                     const double*, const u64*, u32, u64*, u64*) = table <= IDX_TABLE_LDS_MAX ? finalize_pass<true> : finalize_pass<false>;
+                     const double*, const u64*, u32, u32, u32, u64*, u64*) = table <= IDX_TABLE_LDS_MAX ? finalize_pass<true> : finalize_pass<false>;
         hipLaunchKernelGGL(kern, dim3(grid), dim3(256), table <= IDX_TABLE_LDS_MAX ? table : 0, c->stream, g, c->d_bitmap,
                            (const float*)c->d_acc[0], (const float*)c->d_acc[1], c->d_home, out, c->fold ? 0 : 1, (float)g.W,
                            in_place ? 1 : 0, c->d_partials, work, (const double*)c->d_sumsq_rows, (const u64*)c->d_accept_rows,
-                           (u32)(2 * ACCEPT_ROWS), c->d_counters, c->d_mailbox);
+                           c->rows_used[0], c->rows_used[1], (u32)ACCEPT_ROWS, c->d_counters, c->d_mailbox);
     }
     LAUNCH_CHECK(c, "finalize");
     c->n_partials = work;
