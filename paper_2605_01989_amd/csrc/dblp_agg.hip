@@ -724,6 +724,9 @@ __global__ __launch_bounds__(GA_WAVES * WAVE) __attribute__((amdgpu_waves_per_eu
 #ifndef GS_LDS_BUDGET
 #define GS_LDS_BUDGET (48u * 1024u)   // bytes for the two packet buffers
 #endif
+#ifndef GS_WRITER_PREPARES_MAX_W
+#define GS_WRITER_PREPARES_MAX_W 16   // up to this many workers the writer wave also prepares the next group (see the kernel)
+#endif
 #ifndef GS_MAX_PER_CU
 #define GS_MAX_PER_CU 2               // blocks per CU for packets longer than 2 KB (more waves in flight
 #endif                                // only spread the DRAM accesses over more open rows); see apply_batch
@@ -769,14 +772,14 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_wave
     float* acc0, float* acc1, uint8_t* __restrict__ home, u32 pick,
     const u32* __restrict__ block_tallies, u32 n_tally_rows, u64* __restrict__ counters, int whole_batch,
     u64* __restrict__ accept_rows, double* __restrict__ sumsq_rows, float inv_w,
-    u32 sub, u32 sub_log2, u32 n_pass, u32 table_in_lds) {
+    u32 sub, u32 sub_log2, u32 n_pass, u32 table_in_lds, u32 writer_prepares) {
     extern __shared__ float4 sh_dyn[];              // buf[2][sub * stride / 16] float4, slots, bucket table
     __shared__ double sh_sq[GS_READERS];
     __shared__ u64 sh_elem[2][SUB];
     __shared__ u32 sh_len[2][SUB];
     __shared__ u32 sh_home[2][SUB];                 // accumulator copy each packet of the group goes to
-    __shared__ u32 sh_flag_new[2];
-    __shared__ u32 sh_new[GS_READERS], sh_old[GS_READERS];
+    __shared__ u32 sh_new[2][GS_READERS], sh_old[2][GS_READERS];   // per preparing wave: packets of the group that arrived in this batch / in an earlier one
+    __shared__ u32 sh_accepted[GS_READERS + 1];
     __shared__ u32 sh_tally[(GS_READERS + 1) * 5];
     // this launch is the first of the batch's gather launches: its block 0 books the index pass's tallies
     const BatchInfo bi = fold_index_tallies(block_tallies, n_tally_rows, counters, blockIdx.x == 0, sh_tally);
@@ -790,13 +793,15 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_wave
     const u32 upp = g.stride >> 4;                  // float4 units per packet
     float4* buf0 = sh_dyn;
     float4* buf1 = sh_dyn + sub * upp;
-    u32* sh_slot = (u32*)(sh_dyn + 2 * sub * upp);  // [W rounded up to a multiple of 64/sub][sub]
     const u32 wpl = WAVE >> sub_log2;               // workers per 64-lane load of the index
-    // bucket boundaries in LDS when the host made room for them: the span lookup of phase A is
-    // ten dependent loads, and every reader wave waits for it
+    const u32 slot_words = (W + wpl - 1) / wpl * wpl * sub;
+    u32* sh_slot0 = (u32*)(sh_dyn + 2 * sub * upp); // slot tables [W rounded up to a multiple of 64/sub][sub]:
+    u32* sh_slot1 = writer_prepares ? sh_slot0 + slot_words : sh_slot0;   // two when the next group is prepared during this one's gather
+    // bucket boundaries in LDS when the host made room for them (the span lookup of phase A is ten
+    // dependent loads)
     const u32* fs = g.first_seq;
     if (table_in_lds) {
-        u32* tab = sh_slot + (W + wpl - 1) / wpl * wpl * sub;
+        u32* tab = sh_slot1 + slot_words;
         for (u32 i = threadIdx.x; i <= g.B; i += blockDim.x) tab[i] = g.first_seq[i];
         fs = tab;
         __syncthreads();
@@ -809,53 +814,74 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_wave
     u32 accepted = 0;
     double sq = 0.0;      // change of the sum of squares of the stored values caused by this lane's packets
 
+    // ---- phase A of group `ia`: arrival index -> bitmap bits, slots, spans.  The calling wave takes
+    // the index loads w_first, w_first + w_step, ... (wpl workers each) and leaves the group's
+    // flags as seen by it in entry `part`; one of the callers also computes the spans.
+    const u32 n_parts = writer_prepares ? 1u : n_readers;
+    auto phase_a = [&](u32 ia, u32 w_first, u32 w_step, bool spans, u32 part) {
+        const u32 nb_buf = ia & 1;
+        u32* slot_tab = nb_buf ? sh_slot1 : sh_slot0;
+        const u32 seq0 = (grp0 + ia * gridDim.x) << sub_log2;
+        const u32 seq_l = seq0 + s_lane;
+        const u32 word = seq0 >> 6, shift = seq0 & 63;
+        u32 new_or = 0, old_or = 0;
+        for (u32 w0 = w_first; w0 < W; w0 += w_step) {
+            const u32 w = w0 + w_sub;
+            const bool valid = w < W && seq_l < g.n_pkts;
+            u64 p = NONE64, bits = 0;
+            if (valid) {
+                p = pending[(u64)w * g.n_pkts + seq_l];
+                bits = bitmap[(u64)w * g.words_pw + word];
+            }
+            const bool has = p != NONE64;
+            const bool had = valid && ((bits >> (shift + s_lane)) & 1ull);   // delivered by an earlier batch
+            const bool fresh = has && !had;                     // a copy of a delivered packet is dropped
+            const u64 nb = __ballot(fresh);
+            slot_tab[w * sub + s_lane] = fresh ? (u32)p : NONE32;
+            if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty
+            const u32 mine = (u32)(nb >> (w_sub * sub)) & submask;
+            if (s_lane == 0 && mine) atomicOr(&bitmap[(u64)w * g.words_pw + word], (u64)mine << shift);
+            const u64 ob = __ballot(had);
+            for (u32 j = 0; j < wpl; ++j) {
+                new_or |= (u32)(nb >> (j * sub)) & submask;
+                old_or |= (u32)(ob >> (j * sub)) & submask;
+            }
+            accepted += (u32)__popcll(nb);
+        }
+        if (spans && lane < sub && seq_l < g.n_pkts) {
+            const u32 b = find_bucket(fs, g.B, seq_l);
+            const u64 start = (u64)(seq_l - fs[b]) * g.P;
+            const u64 left = g.b_cnt[b] - start;
+            sh_elem[nb_buf][lane] = g.b_off[b] + start;
+            sh_len[nb_buf][lane] = left < g.P ? (u32)left : g.P;
+        }
+        if (lane == 0) { sh_new[nb_buf][part] = new_or; sh_old[nb_buf][part] = old_or; }
+    };
+
+    // Turn `it`, two schedules (the host picks by the number of workers; every LDS table exists
+    // twice, by turn parity):
+    //   writer_prepares   the reader waves gather group it (phase B) while the writer wave drains
+    //                     group it - 1 to the accumulator and then prepares group it + 1 (phase A):
+    //                     the readers never wait for the arrival index; one barrier per turn
+    //   otherwise         the reader waves share phase A of group it while the writer drains group
+    //                     it - 1; barrier; phase B; barrier
+    if (writer_prepares) {
+        if (wave == n_readers && n_it > 0) phase_a(0, 0, wpl, true, 0);
+        __syncthreads();
+    }
     for (u32 it = 0; it <= n_it; ++it) {            // one extra turn so the writer drains the last group
         const u32 cur = it & 1;
         const u32 seq0 = (grp0 + it * gridDim.x) << sub_log2;
         if (wave < n_readers) {
-            if (it < n_it) {
-                // ---- phase A: arrival index -> bitmap bits, slots, spans
-                const u32 seq_l = seq0 + s_lane;
-                const u32 word = seq0 >> 6, shift = seq0 & 63;
-                u32 new_or = 0, old_or = 0;
-                for (u32 w0 = wave * wpl; w0 < W; w0 += n_readers * wpl) {
-                    const u32 w = w0 + w_sub;
-                    const bool valid = w < W && seq_l < g.n_pkts;
-                    u64 p = NONE64, bits = 0;
-                    if (valid) {
-                        p = pending[(u64)w * g.n_pkts + seq_l];
-                        bits = bitmap[(u64)w * g.words_pw + word];
-                    }
-                    const bool has = p != NONE64;
-                    const bool had = valid && ((bits >> (shift + s_lane)) & 1ull);   // delivered by an earlier batch
-                    const bool fresh = has && !had;                     // a copy of a delivered packet is dropped
-                    const u64 nb = __ballot(fresh);
-                    sh_slot[w * sub + s_lane] = fresh ? (u32)p : NONE32;
-                    if (has) pending[(u64)w * g.n_pkts + seq_l] = NONE64;   // leave the index empty
-                    const u32 mine = (u32)(nb >> (w_sub * sub)) & submask;
-                    if (s_lane == 0 && mine) atomicOr(&bitmap[(u64)w * g.words_pw + word], (u64)mine << shift);
-                    const u64 ob = __ballot(had);
-                    for (u32 j = 0; j < wpl; ++j) {
-                        new_or |= (u32)(nb >> (j * sub)) & submask;
-                        old_or |= (u32)(ob >> (j * sub)) & submask;
-                    }
-                    accepted += (u32)__popcll(nb);
-                }
-                if (wave == n_readers - 1 && lane < sub && seq_l < g.n_pkts) {
-                    const u32 b = find_bucket(fs, g.B, seq_l);
-                    const u64 start = (u64)(seq_l - fs[b]) * g.P;
-                    const u64 left = g.b_cnt[b] - start;
-                    sh_elem[cur][lane] = g.b_off[b] + start;
-                    sh_len[cur][lane] = left < g.P ? (u32)left : g.P;
-                }
-                if (lane == 0) { sh_new[wave] = new_or; sh_old[wave] = old_or; }
-            }
-        } else if (it > 0) {
+            if (!writer_prepares && it < n_it) phase_a(it, wave * wpl, n_readers * wpl, wave == n_readers - 1, wave);
+        } else {
+            if (it > 0) {
             // ---- writer: drain group it-1 from LDS to the accumulator (plain aligned stores; a span
             // that earlier batches had written already has its old value folded in by the readers)
             const u32 prev = cur ^ 1;
             const float* src = (const float*)(prev ? buf1 : buf0);
-            const u32 nf = sh_flag_new[prev];
+            u32 nf = 0;
+            for (u32 i = 0; i < n_parts; ++i) nf |= sh_new[prev][i];
             for (u32 t = 0; t < sub; ++t) {
                 if (!((nf >> t) & 1u)) continue;
                 const u64 elem = sh_elem[prev][t];
@@ -878,13 +904,16 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_wave
                     }
                 }
             }
+            }
+            // writes the tables of parity (it + 1) & 1, which the drain above has just read
+            if (writer_prepares && it + 1 < n_it) phase_a(it + 1, 0, wpl, true, 0);
         }
-        __syncthreads();
+        if (!writer_prepares) __syncthreads();
         if (wave < n_readers && it < n_it) {
             // ---- phase B: payload gather, worker order, results to LDS
             u32 new_any = 0, old_any = 0;
-            for (u32 i = 0; i < n_readers; ++i) { new_any |= sh_new[i]; old_any |= sh_old[i]; }
-            if (threadIdx.x == 0) sh_flag_new[cur] = new_any;
+            for (u32 i = 0; i < n_parts; ++i) { new_any |= sh_new[cur][i]; old_any |= sh_old[cur][i]; }
+            const u32* sh_slot = cur ? sh_slot1 : sh_slot0;
             float4* dstbuf = cur ? buf1 : buf0;
             if (NP > 0) {
                 for (u32 t = wave; t < sub; t += n_readers) {
@@ -938,12 +967,16 @@ __global__ __launch_bounds__((GS_READERS + 1) * WAVE) __attribute__((amdgpu_wave
     }
     // accepted packets and sum-of-squares change of this block: plain adds to the block's own rows
     sq = wave_sum_f64(sq);
-    if (wave < n_readers && lane == 0) { sh_new[wave] = accepted; sh_sq[wave] = sq; }
+    if (lane == 0) {
+        sh_accepted[wave] = accepted;               // counted by whichever waves ran phase A
+        if (wave < n_readers) sh_sq[wave] = sq;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {
         u32 total = 0;
         double t = 0.0;
-        for (u32 i = 0; i < n_readers; ++i) { total += sh_new[i]; t += sh_sq[i]; }
+        for (u32 i = 0; i <= n_readers; ++i) total += sh_accepted[i];
+        for (u32 i = 0; i < n_readers; ++i) t += sh_sq[i];
         if (total) { accept_rows[blockIdx.x] += total; sumsq_rows[blockIdx.x] += t; }
     }
 }
@@ -1852,9 +1885,14 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
         const bool launch_direct = !surely_dense;
         if (launch_staged) {   // two groups of packets fit in LDS: readers + writer wave
             const u32 wpl = WAVE / sub;
-            size_t lds = 2ull * sub * g.stride + (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
+            // Up to GS_WRITER_PREPARES_MAX_W workers the writer wave prepares the next group while the
+            // readers gather this one (measured: 4-6 % off the launch with 8 workers, 2 % with 16, but
+            // 3.5 % slower with 32, where the readers share the index loads of a group instead).
+            const u32 writer_prepares = g.W <= GS_WRITER_PREPARES_MAX_W ? 1u : 0u;
+            // two packet buffers, one or two slot tables, and the bucket table when it fits a block's LDS limit
+            size_t lds = 2ull * sub * g.stride + (writer_prepares ? 2 : 1) * (size_t)((g.W + wpl - 1) / wpl * wpl) * sub * sizeof(u32);
             const size_t table = ((size_t)g.B + 1) * sizeof(u32);
-            const u32 table_in_lds = table <= IDX_TABLE_LDS_MAX && lds + table <= 64u * 1024u ? 1u : 0u;   // a block's LDS limit
+            const u32 table_in_lds = table <= IDX_TABLE_LDS_MAX && lds + table <= 64u * 1024u ? 1u : 0u;
             if (table_in_lds) lds += table;
             const u64 groups = ((u64)g.n_pkts + sub - 1) / sub;
             const u32 n_pass = (g.units + WAVE - 1) / WAVE;
@@ -1868,7 +1906,7 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             if (per_cu > 32 / (readers + 1)) per_cu = 32 / (readers + 1);
             if (per_cu > per_cu_max) per_cu = per_cu_max;
             if (per_cu < 1) per_cu = 1;
-            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u32*, u32, u64*, int, u64*, double*, float, u32, u32, u32, u32) =
+            void (*kern)(Geo, const uint8_t*, u64*, u64*, float*, float*, uint8_t*, u32, const u32*, u32, u64*, int, u64*, double*, float, u32, u32, u32, u32, u32) =
                 n_pass == 1 ? gather_accumulate_staged<1> : n_pass == 2 ? gather_accumulate_staged<2>
                 : n_pass == 3 ? gather_accumulate_staged<3> : n_pass == 4 ? gather_accumulate_staged<4>
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
@@ -1877,7 +1915,8 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             hipLaunchKernelGGL(kern, dim3(grid), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
                                c->d_acc[1], c->d_home, (u32)pick, (const u32*)c->d_block_tallies, n_tally_rows, c->d_counters,
-                               surely_dense ? 1 : 0, c->d_accept_rows, c->d_sumsq_rows, inv_w, sub, sub_log2, n_pass, table_in_lds);
+                               surely_dense ? 1 : 0, c->d_accept_rows, c->d_sumsq_rows, inv_w, sub, sub_log2, n_pass, table_in_lds,
+                               writer_prepares);
         }
         if (launch_direct) {   // sparse batches, and packets too long to stage: direct stores from the gathering waves
             const u64 groups = ((u64)g.n_pkts + SUB - 1) / SUB;
