@@ -148,7 +148,8 @@ int dblp_layout(const dblp_ctx* ctx, uint64_t* n_pkts_per_worker, uint32_t* pack
  *   packet buffer of at least 1 GiB is preceded by a timed probe kernel (about 3 ms once per
  *   buffer, synchronising the stream; it reads d_packets[0 .. n_slots * stride) and writes a
  *   scratch area that the library keeps behind each copy) and the answer is remembered for the
- *   last 32 buffers; smaller or thinly used buffers, and contexts with one copy or with
+ *   last 32 buffers (the second copy is chosen when the probe finds it faster by 3 %, plus,
+ *   while results are left in place, what dblp_finalize spends moving its spans to the first); smaller or thinly used buffers, and contexts with one copy or with
  *   caller-owned copies, use the first copy without measuring.  FIRST / SECOND force a copy,
  *   ALTERNATE switches on every batch (for tests).  Select FIRST or SECOND before calling
  *   dblp_apply_arrivals* on a stream that is being captured.

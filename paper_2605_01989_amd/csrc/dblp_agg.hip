@@ -1359,6 +1359,7 @@ struct dblp_ctx {
     u32* d_block_tallies;   // [IDX_BLOCKS_PER_CU * n_cus][5], written by index_arrivals
     u64* d_accept_rows;     // [2][ACCEPT_ROWS] accepted packets per gather block (staged grid, direct grid)
     u32 rows_used[2];       // largest staged / direct gather grid launched in the open round
+    int result_in_place;    // the form of the last dblp_finalize (in place until one says otherwise): prices the second copy
     double* d_sumsq_rows;   // [2][ACCEPT_ROWS] sum of squares of what each gather block stored (same allocation)
     u64* h_mailbox;         // pinned host memory, 16 x u64, also mapped into the device
     u64* d_mailbox;         // device address of h_mailbox
@@ -1569,7 +1570,16 @@ static int pick_copy(dblp_ctx* c, const void* d_packets, u64 bytes, u64 n_slots,
     const float t0 = measure(c->d_scratch[0]);
     if (t0 < 0.f) return 0;
     const float t1 = measure(c->d_scratch[1]);
-    const int pick = t1 > 0.f && t1 < 0.97f * t0 ? 1 : 0;
+    // The second copy has to be that much faster: 3 % when the result is copied out of the
+    // accumulator anyway; when it is left in place, spans written to the second copy are moved to
+    // the first by finalize (8 bytes per element, at about two thirds of the gather's rate, against
+    // the 4 W (1 + 2/P) + 4 bytes per element that the gather moves).
+    float margin = 0.03f;
+    if (c->result_in_place) {
+        const float gather_bytes = 4.f * (float)c->g.W * (1.f + 2.f / (float)c->g.P) + 4.f;
+        margin += 1.5f * 8.f / gather_bytes;
+    }
+    const int pick = t1 > 0.f && t1 < (1.f - margin) * t0 ? 1 : 0;
     dblp_ctx::Picked& slot = c->picked[c->n_picked < 32 ? c->n_picked++ : c->batch_no % 32];
     slot.p = d_packets; slot.bytes = bytes; slot.pick = pick;
     return pick;
@@ -1617,6 +1627,7 @@ extern "C" int dblp_create(dblp_ctx** out, const dblp_config* cfg) {
     c->search_fraction = cfg->search_free_fraction > 0.0 ? cfg->search_free_fraction : 0.5;
     c->search_seconds = cfg->search_seconds > 0.0 ? cfg->search_seconds : 2.0;
     c->fold = (cfg->n_workers & (cfg->n_workers - 1)) == 0;
+    c->result_in_place = c->fold ? 1 : 0;     // the in-place finalize exists for power-of-two worker counts
     c->timed = new (std::nothrow) std::vector<dblp_ctx::Timed>();
     c->ev_pool = new (std::nothrow) std::vector<hipEvent_t>();
     if (!c->timed || !c->ev_pool) { dblp_destroy(c); return DBLP_ENOMEM; }
@@ -2016,6 +2027,7 @@ extern "C" int dblp_finalize(dblp_ctx* c, int compensation, float* d_out) {
                            c->rows_used[0], c->rows_used[1], (u32)ACCEPT_ROWS, c->d_counters, c->d_mailbox);
     }
     LAUNCH_CHECK(c, "finalize");
+    c->result_in_place = in_place ? 1 : 0;
     c->n_partials = work;
     c->finalized = 1;
     c->norm_in_mailbox = c->fold;
