@@ -73,7 +73,8 @@ class DeviceJob:
         self.both_forms_its = set(both_forms_its)
         self.picks = None    # a list here collects the accumulator copy each receive-queue batch wrote new spans to
         self.rnd_id = 1
-        mode = dict(one=binding.ACCMODE_SINGLE, pair=binding.ACCMODE_PAIR, search=binding.ACCMODE_SEARCH)[accumulator]
+        mode = dict(one=binding.ACCMODE_SINGLE, trial=binding.ACCMODE_SINGLE, pair=binding.ACCMODE_PAIR,
+                    search=binding.ACCMODE_SEARCH)[accumulator]
         self.agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5),
                                    accumulator_mode=mode, search_free_fraction=0.6, search_seconds=8.0)
         self.n_slots = L.W * L.n_pkts
@@ -288,10 +289,59 @@ class DeviceJob:
         return dict(rounds=rounds, resent=resent, norm=norm, rel_delta=delta, critical=crit, lost_first=m["lost"])
 
 
+def place_accumulator_by_trial(job, w, n_candidates: int = 8, hold_fraction: float = 0.8) -> dict:
+    """Set-up, before any timed step: where the accumulator lies relative to the resident packets
+    decides several percent of the step, and only a measurement can tell (the physical layout of an
+    allocation cannot be asked for).  So the caller does what a long-running receiver would do at
+    start-up: it offers the library caller-owned accumulators at several places (buffers spread over
+    the free memory, at most hold_fraction of it held at once), runs one untimed and one timed
+    step with each, the library's own allocation included, and keeps the fastest.  The
+    library is not involved beyond accepting the caller's buffer."""
+    import torch
+    import paper_2605_01989_amd as dblp
+    from paper_2605_01989_amd import binding
+    L = job.L
+    n_bytes = 4 * L.N
+    ctx_bytes = int(1.25 * 8 * L.W * L.n_pkts) + (64 << 20)       # a context's arrival index and small tables
+    budget = int(torch.cuda.mem_get_info()[0] * hold_fraction)
+    k_max = min(n_candidates, budget // (n_bytes + ctx_bytes))
+    gap = max(0, (budget - k_max * (n_bytes + ctx_bytes)) // max(k_max, 1)) & ~((2 << 20) - 1)
+
+    def timed_step():
+        job.next_bound = first_bound(w)
+        run_leg(job, w, [0])
+        return run_leg(job, w, [0])["event_ms"]
+
+    tried = [dict(where="library", ms=round(timed_step(), 3), agg=job.agg, acc=None)]
+    fillers = []
+    for k in range(k_max):
+        acc = torch.empty(L.N, dtype=torch.float32, device="cuda")
+        agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5),
+                              accumulator_mode=binding.ACCMODE_SINGLE, d_accumulator=(acc, None))
+        job.agg = agg
+        if job.in_place:
+            job.d_out = acc
+        tried.append(dict(where=f"{(acc.data_ptr() - job.packets.data_ptr()) / 2**30:+.1f} GiB from the packets",
+                          ms=round(timed_step(), 3), agg=agg, acc=acc))
+        if gap:
+            fillers.append(torch.empty(gap, dtype=torch.uint8, device="cuda"))
+    best = min(tried, key=lambda t: t["ms"])
+    job.agg = best["agg"]
+    if job.in_place:
+        job.d_out = best["acc"] if best["acc"] is not None else job.agg.accumulator_tensor(0)
+    report = dict(candidates=[dict(where=t["where"], ms=t["ms"]) for t in tried], adopted=best["where"])
+    for t in tried:
+        if t is not best:
+            t["agg"] = t["acc"] = None
+    del tried, fillers
+    torch.cuda.empty_cache()
+    return report
+
+
 def default_accumulator(w) -> str:
-    """A second accumulator copy is worth its memory when one round carries at least 2 GiB of packets."""
+    """Placing the accumulator by trial pays when one round carries at least 2 GiB of packets."""
     L = w.layout
-    return "search" if L.W * L.n_pkts * L.stride >= 2 << 30 else "one"
+    return "trial" if L.W * L.n_pkts * L.stride >= 2 << 30 else "one"
 
 
 def next_bound(w, rel_delta: float, critical: bool) -> int:
@@ -425,10 +475,12 @@ def main():
     ap.add_argument("--arrivals", default="queue", choices=["queue", "tables"],
                     help="how first transmissions are handed over: one receive queue of descriptors per "
                          "chunk step (default), or mask + order + per-slot worker table")
-    ap.add_argument("--accumulator", default=None, choices=["search", "pair", "one"],
+    ap.add_argument("--accumulator", default=None, choices=["search", "pair", "one", "trial"],
                     help="search: a second accumulator copy is searched for in another third of HBM (bounded; "
-                         "one copy when none is found); pair: a plain second copy; one: a single copy.  "
-                         "Default: search when a round carries at least 2 GiB of packets, else one")
+                         "one copy when none is found); pair: a plain second copy; one: a single copy; trial: a "
+                         "single caller-owned copy at the best of several places, found by timing one step with each "
+                         "before the warm-up.  "
+                         "Default: trial when a round carries at least 2 GiB of packets, else one")
     ap.add_argument("--extra-steps", type=int, default=5,
                     help="steps of the timed run that are replayed (same masks, same bounds) with the other "
                          "hand-over form and with a single accumulator copy, reported under other_forms; 0 = none")
@@ -458,6 +510,11 @@ def main():
     form = {"queue": True, "tables": False}
     job = DeviceJob(w, n_masks=total, place=args.place, order=args.order, queue=form[args.arrivals],
                     accumulator=args.accumulator, both_forms_its=extra_its)
+    trial = None
+    if args.accumulator == "trial":
+        trial = place_accumulator_by_trial(job, w)
+        for t in trial["candidates"]:
+            log(f"[bench] accumulator trial: {t['where']}: {t['ms']} ms")
     agg = job.agg
 
     if args.calibrate_copy:
@@ -502,6 +559,8 @@ def main():
     acc_info = agg.accumulator_info()
     acc_info.pop("last_pick")
     acc_info["mode"] = args.accumulator
+    if trial:
+        acc_info["trial"] = trial
     acc_info["copy_per_chunk_step"] = "".join(str(p) for p in picks)
 
     def leg_summary(leg):
