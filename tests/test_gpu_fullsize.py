@@ -153,7 +153,11 @@ def test_full_size_sampled_buckets_and_global_properties(name, BOUND_PPM, extra)
     import torch
     import bench
     w = wl.workload(name)
-    job = bench.DeviceJob(w, n_masks=1, accumulator=bench.default_accumulator(w))   # as bench.py runs it
+    mode = bench.default_accumulator(w)
+    job = bench.DeviceJob(w, n_masks=1, accumulator=mode)                           # as bench.py runs it:
+    if mode == "trial":                                                             # on a caller-owned accumulator
+        placed = bench.place_accumulator_by_trial(job, w, n_candidates=2)           # chosen among a few places
+        assert placed["adopted"] in [c["where"] for c in placed["candidates"]] and len(placed["candidates"]) == 3
     L = job.L
     probes = []
     res = job.step(0, BOUND_PPM, record=probes)
