@@ -34,8 +34,8 @@ BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; late
 # on and by workload; anything else reports null.
 # value = measured bytes / algorithmic bytes of a first-transmission launch.
 PMC_TRAFFIC_RATIO: dict[tuple[str, str], float] = {
-    ("ad5c8e0e5e9fde1fb1d0e071cd149a1c7098fb13d75bc391031524bf458121dc", "cfg5"): 1.066,   # profiles/receiver_path_cfg5.md
-    ("ad5c8e0e5e9fde1fb1d0e071cd149a1c7098fb13d75bc391031524bf458121dc", "cfg4"): 1.030,   # profiles/receiver_path_cfg4.md
+    ("47046a5c9c4e47dcf42b4510f74a52c4da4ca2d1117718669783fc31c3d4abbf", "cfg5"): 1.066,   # profiles/receiver_path_cfg5.md
+    ("47046a5c9c4e47dcf42b4510f74a52c4da4ca2d1117718669783fc31c3d4abbf", "cfg4"): 1.030,   # profiles/receiver_path_cfg4.md
 }
 
 
