@@ -348,6 +348,43 @@ def test_multiple_batches_accumulate_into_existing_spans(queue):
     assert (np.abs(got - ref)[nz] / scale[nz]).max() <= FLOAT_TOL and np.all(got[~nz] == 0)
 
 
+@pytest.mark.parametrize("W,n_elems", [(2, 1_200_000), (20, 120_000)])
+def test_small_batches_scattered_over_a_long_round(W, n_elems):
+    """A dense first batch, then batches of a handful of packets scattered over a round of up to 1.2 M
+    sequence numbers (the direct gather looks through the arrival index of many groups at once and
+    walks the few that hold an entry: more than 64 groups per block at the larger size), a batch that
+    fills a contiguous run, and one that is mostly copies of delivered packets."""
+    sc = build_scenario(mk(W, [n_elems, 37], 1, place="worker_major", order="identity"))
+    L = sc.L
+    n = L.W * L.n_pkts
+    rng = np.random.default_rng(11)
+    run = np.arange(5000, 5300, dtype=np.int64)                        # 300 consecutive packets of worker 0
+    held = np.unique(np.concatenate([rng.choice(n, size=1700, replace=False), run]))
+    first = np.setdiff1d(np.arange(n, dtype=np.int64), held)
+    scattered = rng.choice(np.setdiff1d(held, run), size=40, replace=False)
+    batches = [rng.permutation(first), scattered[:12], run, scattered[12:28],
+               np.concatenate([rng.choice(first, size=50, replace=False), scattered[28:33]])]
+    o, g = both(sc)
+    for rx in (o, g):
+        rx.begin_round(sc.rnd_id)
+        for b in batches:
+            rx.apply(0, n, None, b.astype(np.uint32))
+    delivered = np.ones(n, dtype=bool)
+    delivered[np.setdiff1d(held, np.concatenate([run, scattered[:33]]))] = False
+    assert np.array_equal(o.bitmap().reshape(-1).astype(bool), delivered)
+    assert np.array_equal(g.bitmap(), o.bitmap())
+    assert g.counters() == o.counters() and o.counters()["duplicate"] == 50
+    m_o, l_o, c_o, met_o = o.loss_account(0)
+    m_g, l_g, c_g, met_g = g.loss_account(0)
+    assert c_g == c_o == int((~delivered).sum()) and np.array_equal(m_g, m_o) and np.array_equal(l_g[:c_g], l_o[:c_o])
+    ref, got = o.finalize(), g.finalize().astype(np.float64)
+    from harness import abs_scale
+    scale = abs_scale(sc, delivered.reshape(L.W, L.n_pkts).astype(np.uint8))
+    nz = scale > 0
+    assert (np.abs(got - ref)[nz] / scale[nz]).max() <= FLOAT_TOL and np.all(got[~nz] == 0)
+    assert abs(g.phase_signal()[0] - o.phase_signal()[0]) <= 1e-6 * o.phase_signal()[0] + 2.0 ** -22 * np.sqrt((scale ** 2).sum())
+
+
 @pytest.mark.parametrize("queue", [False, True])
 def test_stale_duplicate_and_invalid_packets(queue):
     sc = build_scenario(mk(2, [100, 7], 10, place="worker_major", order="identity"))
