@@ -330,7 +330,8 @@ def place_accumulator_by_trial(job, w, n_candidates: int = 8, hold_fraction: flo
     if job.in_place:
         job.d_out = best["acc"] if best["acc"] is not None else job.agg.accumulator_tensor(0)
     report = dict(candidates=[dict(where=t["where"], ms=t["ms"]) for t in tried], adopted=best["where"])
-    for t in tried:
+    job.plain_agg = tried[0]["agg"] if tried[0] is not best else None    # kept for the single-plain-copy leg of other_forms
+    for t in tried[1:]:
         if t is not best:
             t["agg"] = t["acc"] = None
     del tried, fillers
@@ -587,6 +588,13 @@ def main():
         if acc_info["copies"] == 2:
             job.use_single_accumulator()
             run_leg(job, w, extra_its[:1], bounds)          # one untimed step on the new copy
+            other[f"{args.arrivals}+one"] = leg_summary(run_leg(job, w, extra_its, bounds))
+        elif getattr(job, "plain_agg", None) is not None:
+            # the same steps on the context the job started with: one copy, where the library's allocation fell
+            job.agg = job.plain_agg
+            if job.in_place:
+                job.d_out = job.agg.accumulator_tensor(0)
+            run_leg(job, w, extra_its[:1], bounds)
             other[f"{args.arrivals}+one"] = leg_summary(run_leg(job, w, extra_its, bounds))
 
     out = dict(metric="aggregated_gradient_GBps", value=round(value, 2), unit="GB/s", n_gpus=1,
