@@ -27,6 +27,13 @@
  *     into: a context with TWO library-owned accumulator copies under the
  *     policy DBLP_ACC_AUTO times a probe kernel the first time it sees a packet
  *     buffer of 1 GiB or more (see "The accumulator and where it lives").
+ *   - dblp_begin_round, dblp_apply_arrivals* (outside the exception above) and
+ *     dblp_finalize only launch kernels on the context's stream, so a caller may
+ *     record a round of them into a HIP graph by stream capture and replay it
+ *     (tested: replays give the bits of the eager run).  The context's host-side
+ *     bookkeeping is done when the calls are made, i.e. at capture: replay the
+ *     recorded round as a whole, and call the functions that return host scalars
+ *     outside the capture, after a replay.
  *   - A context is not thread-safe; use one per host thread.
  *
  * Geometry.  The gradient has N fp32 elements, tiled in order by B buckets

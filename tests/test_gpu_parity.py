@@ -348,6 +348,47 @@ def test_multiple_batches_accumulate_into_existing_spans(queue):
     assert (np.abs(got - ref)[nz] / scale[nz]).max() <= FLOAT_TOL and np.all(got[~nz] == 0)
 
 
+def test_a_round_recorded_under_stream_capture_replays_to_the_eager_result():
+    """begin_round, the batches of a round and finalize only launch kernels on the context's stream,
+    so a caller may record them into a graph: three replays, with eager work of the program between
+    them, each give the bits and the counters of the eager run."""
+    import torch
+    sc = build_scenario(mk(8, [366 * 300 + 5, 4000, 77], 366, 0.05))
+    L = sc.L
+    eager = GpuRx(sc); eager.packetize_all()
+    eager.begin_round(sc.rnd_id)
+    for b in sc.batches:
+        eager.apply(b.slot_base, b.n_slots, b.mask, b.order)
+    want = eager.finalize().copy()
+    want_norm, want_counters, want_bitmap = eager.phase_signal()[0], eager.counters(), eager.bitmap()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        g = GpuRx(sc)                      # its context takes the current stream: the side stream
+        g.packetize_all()
+        st = g.agg.stride
+        dev = [(b, None if b.mask is None else torch.from_numpy(b.mask.view(np.int64)).cuda(),
+                None if b.order is None else torch.from_numpy(np.asarray(b.order, dtype=np.uint32).view(np.int32)).cuda())
+               for b in sc.batches]
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            g.agg.begin_round(sc.rnd_id)
+            for b, d_mask, d_order in dev:
+                g.agg.apply_arrivals(g.packets[b.slot_base * st:], g.src[b.slot_base:], b.n_slots, d_mask, d_order,
+                                     b.n_slots if d_order is None else d_order.numel())
+            g.agg.finalize(g.d_out)
+        for rep in range(3):
+            g.d_out.fill_(7.0)             # eager work between the replays
+            torch.cuda.synchronize()
+            graph.replay()
+            side.synchronize()
+            got = g.d_out.cpu().numpy()
+            assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), f"replay {rep}"
+            assert g.phase_signal()[0] == want_norm and g.counters() == want_counters, f"replay {rep}"
+            assert np.array_equal(g.bitmap(), want_bitmap), f"replay {rep}"
+            g.agg.set_prev_norm(None)
+
+
 @pytest.mark.parametrize("W,n_elems", [(2, 1_200_000), (20, 120_000)])
 def test_small_batches_scattered_over_a_long_round(W, n_elems):
     """A dense first batch, then batches of a handful of packets scattered over a round of up to 1.2 M
