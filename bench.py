@@ -315,16 +315,23 @@ def place_accumulator_by_trial(job, w, n_candidates: int = 8, hold_fraction: flo
     tried = [dict(where="library", ms=round(timed_step(), 3), agg=job.agg, acc=None)]
     fillers = []
     for k in range(k_max):
-        acc = torch.empty(L.N, dtype=torch.float32, device="cuda")
-        agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5),
-                              accumulator_mode=binding.ACCMODE_SINGLE, d_accumulator=(acc, None))
+        try:
+            acc = torch.empty(L.N, dtype=torch.float32, device="cuda")
+            agg = dblp.Aggregator(L.W, L.N, L.P, L.bucket_off, L.bucket_cnt, w.policy.get("eta", 0.5),
+                                  accumulator_mode=binding.ACCMODE_SINGLE, d_accumulator=(acc, None))
+        except (RuntimeError, dblp.DblpError) as e:      # out of memory: make do with the places tried so far
+            log(f"[bench] accumulator trial stops after {k} places: {e}")
+            break
         job.agg = agg
         if job.in_place:
             job.d_out = acc
         tried.append(dict(where=f"{(acc.data_ptr() - job.packets.data_ptr()) / 2**30:+.1f} GiB from the packets",
                           ms=round(timed_step(), 3), agg=agg, acc=acc))
         if gap:
-            fillers.append(torch.empty(gap, dtype=torch.uint8, device="cuda"))
+            try:
+                fillers.append(torch.empty(gap, dtype=torch.uint8, device="cuda"))
+            except RuntimeError:
+                break
     best = min(tried, key=lambda t: t["ms"])
     job.agg = best["agg"]
     if job.in_place:
