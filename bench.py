@@ -34,8 +34,8 @@ BENCH_DRAWN_ROUNDS = 3   # retransmission rounds with a drawn loss pattern; late
 # on and by workload; anything else reports null.
 # value = measured bytes / algorithmic bytes of a first-transmission launch.
 PMC_TRAFFIC_RATIO: dict[tuple[str, str], float] = {
-    ("47046a5c9c4e47dcf42b4510f74a52c4da4ca2d1117718669783fc31c3d4abbf", "cfg5"): 1.066,   # profiles/receiver_path_cfg5.md
-    ("47046a5c9c4e47dcf42b4510f74a52c4da4ca2d1117718669783fc31c3d4abbf", "cfg4"): 1.030,   # profiles/receiver_path_cfg4.md
+    ("3d4a1fc4cec74112deff2e5e7730b9e8e47595d4a41a9e5ff7a7fd105506a6c6", "cfg5"): 1.066,   # profiles/receiver_path_cfg5.md
+    ("3d4a1fc4cec74112deff2e5e7730b9e8e47595d4a41a9e5ff7a7fd105506a6c6", "cfg4"): 1.030,   # profiles/receiver_path_cfg4.md
 }
 
 
@@ -440,7 +440,7 @@ def run_leg(job, w, its, bounds=None, profile=False) -> dict:
 
     if profile:
         agg.profile_enable(profile)
-        for k in range(binding.K_FINALIZE + 1):
+        for k in range(binding.K_COUNT):
             agg.profile_read(k)
     torch.cuda.synchronize()
     accepted_total, resent_total, rounds_total = 0, 0, 0
@@ -466,8 +466,8 @@ def run_leg(job, w, its, bounds=None, profile=False) -> dict:
                per_step=per_step, event_ms=ev0.elapsed_time(ev1))
     if profile:
         out["prof"] = {name: agg.profile_read(k) for name, k in
-                       (("index", binding.K_INDEX), ("gather", binding.K_GATHER), ("probe", binding.K_PROBE),
-                        ("finalize", binding.K_FINALIZE))}
+                       (("index", binding.K_INDEX), ("gather", binding.K_GATHER), ("gather_direct", binding.K_GATHER_DIRECT),
+                        ("probe", binding.K_PROBE), ("finalize", binding.K_FINALIZE))}
         agg.profile_enable(False)
     return out
 
@@ -539,8 +539,10 @@ def main():
     for st in warm["per_step"]:
         log(f"[bench] warmup {st['it']}: bound={st['bound_ppm']} rounds={st['rounds']}")
     from paper_2605_01989_amd import binding
-    # the timed region brackets only the dominant kernel group with events (two event records per
-    # batch); the per-group breakdown comes from a replay of its first steps with every group bracketed
+    # the timed region brackets only the launches of the dominant kernel, the staged gather, with events
+    # (two event records per dense batch; the direct kernel's launches on sparse retransmission batches
+    # are a group of their own); the per-group breakdown comes from a replay of its first steps with
+    # every group bracketed
     main_leg = run_leg(job, w, list(range(args.warmup, total)), profile=1 << binding.K_GATHER)
     wall, prof = main_leg["wall"], main_leg["prof"]
     accepted_total = main_leg["accepted"]
@@ -548,10 +550,13 @@ def main():
 
     fill = L.N / (L.n_pkts * L.P)
     value = accepted_total * 4 * L.P * fill / wall / 1e9
-    # dominant kernel: gather_accumulate.  Algorithmic bytes = every accepted packet read once
-    # (header + payload + padding = stride) + the accumulator written once per iteration.
+    # dominant kernel: gather_accumulate_staged, which takes the first transmissions (a retransmission
+    # batch goes to the direct kernel unless it is dense; one that the staged kernel does take adds its
+    # time here and not its bytes).  Algorithmic bytes = every packet accepted from a first transmission
+    # read once (header + payload + padding = stride) + the accumulator written once per iteration.
     g_ms, g_n = prof["gather"]
-    g_bytes = accepted_total * L.stride + args.steps * 4 * L.N
+    first_accepted = accepted_total - main_leg["resent"]
+    g_bytes = first_accepted * L.stride + args.steps * 4 * L.N
     achieved = g_bytes / (g_ms * 1e-3) / 1e9 if g_ms > 0 else 0.0
     ratio_pmc = PMC_TRAFFIC_RATIO.get((_kernel_source_hash(), w.name))
     roofline = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBPS, unit="GB/s",
@@ -562,8 +567,8 @@ def main():
     # whole-path algorithmic bytes: the gather's (packets read once, accumulator written once).  The
     # mean and the sum of squares are formed in the same pass and the result is left in place, so the
     # compensation pass adds no bytes of its own beyond the spans it zeroes or moves.
-    path_bytes = g_bytes
-    separate_pass_bytes = g_bytes + args.steps * 8 * L.N     # what a separate read-scale-write finalize pass would add
+    path_bytes = accepted_total * L.stride + args.steps * 4 * L.N
+    separate_pass_bytes = path_bytes + args.steps * 8 * L.N     # what a separate read-scale-write finalize pass would add
     acc_info = agg.accumulator_info()
     acc_info.pop("last_pick")
     acc_info["mode"] = args.accumulator

@@ -297,16 +297,17 @@ int dblp_set_prev_norm(dblp_ctx* ctx, double norm, int have);
 int dblp_get_prev_norm(const dblp_ctx* ctx, double* h_norm, int* h_have);
 
 /* Optional tracing: `on` is a bit mask of kernel groups (bit DBLP_K_* set = the launches of that
- * group are bracketed by HIP events on the context's stream; 0 = off, 15 = all four; a bracket
- * costs two event records, which shows on small rounds).  dblp_profile_read synchronises the stream, returns
+ * group are bracketed by HIP events on the context's stream; 0 = off, 31 = all five; a bracket
+ * costs two event records, 10-17 us of the stream's time, which shows on small rounds).  dblp_profile_read synchronises the stream, returns
  * the summed duration (milliseconds) and number of launches recorded for one kernel group
  * since the last read of that group, and forgets them.  At most 16384 brackets are kept between
  * reads; further ones are dropped.  dblp_profile_enable may return ENOMEM. */
 #define DBLP_K_INDEX 0    /* header parse / validation / arrival index */
-#define DBLP_K_GATHER 1   /* payload gather + accumulate */
+#define DBLP_K_GATHER 1   /* payload gather + accumulate, staged kernel (dense batches) */
 #define DBLP_K_PROBE 2    /* loss count + prefix + retransmit list (three launches, one bracket) */
 #define DBLP_K_FINALIZE 3 /* zero-fill mean + partial sums of squares */
-#define DBLP_K_COUNT 4
+#define DBLP_K_GATHER_DIRECT 4 /* the same, direct kernel (sparse batches, packets too long to stage) */
+#define DBLP_K_COUNT 5
 int dblp_profile_enable(dblp_ctx* ctx, int on);
 int dblp_profile_read(dblp_ctx* ctx, int kernel, double* h_total_ms, uint64_t* h_launches);
 

@@ -17,7 +17,8 @@ OK, EINVAL, ENOMEM, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4, -5
 _NAMES = {EINVAL: "DBLP_EINVAL", ENOMEM: "DBLP_ENOMEM", ECAPACITY: "DBLP_ECAPACITY",
           ESTATE: "DBLP_ESTATE", EHIP: "DBLP_EHIP"}
 COMP_ZEROFILL_MEAN = 0
-K_INDEX, K_GATHER, K_PROBE, K_FINALIZE = 0, 1, 2, 3
+K_INDEX, K_GATHER, K_PROBE, K_FINALIZE, K_GATHER_DIRECT = 0, 1, 2, 3, 4
+K_COUNT = 5
 ACC_AUTO, ACC_FIRST, ACC_SECOND, ACC_ALTERNATE = 0, 1, 2, 3
 ACCMODE_SINGLE, ACCMODE_PAIR, ACCMODE_SEARCH = 0, 1, 2
 
@@ -277,7 +278,7 @@ class Aggregator:
 
     def profile_enable(self, on):
         """on: False/0 off, True all kernel groups, or a bit mask (1 << K_GATHER, ...)."""
-        self._check(lib().dblp_profile_enable(self._h, 15 if on is True else int(on)))
+        self._check(lib().dblp_profile_enable(self._h, (1 << K_COUNT) - 1 if on is True else int(on)))
 
     def profile_read(self, kernel: int):
         """(total milliseconds, launches) of one kernel group since the last read."""

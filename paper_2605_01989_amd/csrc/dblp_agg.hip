@@ -1879,7 +1879,6 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
     }
     const float inv_w = c->fold ? 1.0f / (float)g.W : 1.0f;   // exact for the powers of two it is used with
     {
-        ProfScope ps(c, DBLP_K_GATHER);
         u32 sub = SUB, sub_log2 = 4;
         while (sub >= 2 && 2u * sub * g.stride > GS_LDS_BUDGET) { sub >>= 1; --sub_log2; }
         // Which gather kernel: the staged one for dense batches, the direct one for sparse ones
@@ -1923,6 +1922,7 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
                 : n_pass == 5 ? gather_accumulate_staged<5> : gather_accumulate_staged<0>;
             const u32 grid = grid_for(c, groups, per_cu);
             if (grid > c->rows_used[0]) c->rows_used[0] = grid;
+            ProfScope ps(c, DBLP_K_GATHER);
             hipLaunchKernelGGL(kern, dim3(grid), dim3((readers + 1) * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
                                c->d_acc[1], c->d_home, (u32)pick, (const u32*)c->d_block_tallies, n_tally_rows, c->d_counters,
@@ -1937,6 +1937,7 @@ static int apply_batch(dblp_ctx* c, const void* d_packets, const uint16_t* d_src
             if (table_in_lds) lds += table;
             const u32 grid = grid_for(c, groups, GA_BLOCKS_PER_CU);
             if (grid > c->rows_used[1]) c->rows_used[1] = grid;
+            ProfScope ps(c, DBLP_K_GATHER_DIRECT);
             hipLaunchKernelGGL(gather_accumulate, dim3(grid), dim3(GA_WAVES * WAVE),
                                lds, c->stream, g, (const uint8_t*)d_packets, c->d_pending, c->d_bitmap, c->d_acc[0],
                                c->d_acc[1], c->d_home, (u32)pick, (const u32*)c->d_block_tallies, n_tally_rows, c->d_counters,
