@@ -28,6 +28,21 @@ def test_library_exports_every_declared_symbol():
     assert sorted(binding.EXPORTS) == names
 
 
+def test_binding_constants_mirror_the_header():
+    """Every integer #define of the header that the binding names has the header's value."""
+    text = open(os.path.join(ROOT, "include", "dblp_agg.h")).read()
+    defines = {m.group(1): int(m.group(2)) for m in re.finditer(r"^#define\s+DBLP_([A-Z_0-9]+)\s+\(?(-?\d+)\)?", text, flags=re.M)}
+    assert len(defines) >= 20
+    checked = 0
+    for name, value in defines.items():
+        if hasattr(binding, name):
+            assert getattr(binding, name) == value, name
+            checked += 1
+    for must in ("OK", "EINVAL", "ESTATE", "K_GATHER", "K_GATHER_DIRECT", "K_COUNT", "ACC_AUTO", "ACCMODE_SEARCH", "COMP_ZEROFILL_MEAN"):
+        assert must in defines and hasattr(binding, must), must
+    assert checked >= 15
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2605_01989_amd")
     for dirpath, _, files in os.walk(pkg):
